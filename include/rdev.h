@@ -1,0 +1,257 @@
+/*
+ * rdev.h - C ABI of the memory-region "device" for cross-partition tensor transfer.
+ *
+ * The paper (abstract, section 1, section 3.1) replaces RPC by a device-like
+ * interface: a remote machine is a *device* on which memory regions can be
+ * allocated, read and written, and a transfer is a memory copy between a local
+ * and a remote region.  Here one GPU plays both ends: sender tensors and
+ * receiver regions live in separate registered arenas of the same HBM, and the
+ * copy engine is a HIP kernel instead of a NIC.
+ *
+ * Conventions
+ *   - Every function returns rdev_status: RDEV_OK (0), RDEV_NOT_READY (1, only
+ *     from rdev_poll, not an error) or a negative RDEV_E_* code.  Nothing is
+ *     thrown across the boundary.  rdev_last_error() gives a human-readable
+ *     string for the last failure on the calling thread.
+ *   - "device pointer" = address in GPU memory; "host pointer" = ordinary
+ *     process memory.  Each argument says which one it is.
+ *   - Arenas and source tensors are owned by the caller and must outlive every
+ *     plan that names them.  Plans, descriptor tables and the pinned host words
+ *     that mirror flags are owned by the library.
+ *   - All sizes and offsets are 64-bit.
+ *   - Transfers are asynchronous: they are enqueued on the caller's HIP stream
+ *     (a hipStream_t passed as void*, NULL = the null stream) and the call
+ *     returns.  Completion is observed with rdev_poll (per-tensor flags) or by
+ *     synchronising the stream.
+ *   - No consumed-acknowledgement exists (section 4): the caller issues the
+ *     next write of a tensor only after the receiver has consumed the previous
+ *     one.  A plan created with RDEV_PLAN_CHECK_BUSY reports RDEV_E_BUSY instead
+ *     of overwriting an unconsumed tensor.
+ *   - Calls on one rdev_device / rdev_plan are not thread-safe against each
+ *     other, except rdev_poll without RDEV_POLL_CONSUME, which only reads.
+ */
+#ifndef RDEV_H
+#define RDEV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RDEV_MAX_DIMS       8
+#define RDEV_META_BYTES     128
+#define RDEV_DEFAULT_ALIGN  256
+#define RDEV_ALL_TENSORS    0xFFFFFFFFu
+#define RDEV_HOST_ONLY      (-1)
+
+typedef int32_t rdev_status;
+enum {
+    RDEV_OK          = 0,
+    RDEV_NOT_READY   = 1,
+    RDEV_E_INVAL     = -1,  /* bad argument: null pointer, unknown id, rank > RDEV_MAX_DIMS, dim < -1, unknown dtype/mode */
+    RDEV_E_NOMEM     = -2,  /* region, plan, heap or message buffer does not fit */
+    RDEV_E_OVERLAP   = -3,  /* a source range overlaps its own destination range */
+    RDEV_E_ALIGN     = -4,  /* alignment not a power of two (plans: also < 16) */
+    RDEV_E_RANGE     = -5,  /* address not inside a registered arena */
+    RDEV_E_OVERFLOW  = -6,  /* dims product or an offset does not fit 64 bits */
+    RDEV_E_BUSY      = -7,  /* unconsumed flag (RDEV_PLAN_CHECK_BUSY), or arena still referenced */
+    RDEV_E_HIP       = -8,  /* a HIP call failed, or a transfer was requested on a host-only device */
+    RDEV_E_STATE     = -9   /* call out of protocol order (sources not bound, metadata not polled, ...) */
+};
+
+/* element types carried in the metadata record (section 3.3: "the element data type") */
+enum {
+    RDEV_U8 = 0, RDEV_I8 = 1, RDEV_I16 = 2, RDEV_I32 = 3, RDEV_I64 = 4,
+    RDEV_F16 = 5, RDEV_BF16 = 6, RDEV_F32 = 7, RDEV_F64 = 8
+};
+
+enum { RDEV_STATIC = 0, RDEV_DYNAMIC = 1 };
+
+/* transfer modes of rdev_write_batch */
+enum {
+    RDEV_ZEROCOPY   = 0,  /* section 3.2: one-sided write into the pre-allocated region */
+    RDEV_RPC2       = 1,  /* section 2.2: pack header+payload into a message buffer, unpack into a fresh allocation */
+    RDEV_RPC3       = 2,  /* section 5.1 (RPC over RDMA): as RPC2 plus a buffer-to-buffer copy in between */
+    RDEV_SENDERCOPY = 3   /* section 5.1 (analysis off): stage into a registered buffer, then zero-copy write */
+};
+
+enum { RDEV_POLL_CONSUME = 1, RDEV_POLL_META = 2, RDEV_POLL_ARENA = 4 };
+enum { RDEV_PLAN_CHECK_BUSY = 1 };
+
+typedef struct rdev_device_s rdev_device_t;
+typedef struct rdev_plan_s   rdev_plan_t;
+
+typedef struct {
+    uint32_t arena_id;
+    uint32_t _pad;
+    uint64_t offset;    /* bytes from the arena base */
+    uint64_t bytes;
+} rdev_region;
+
+/* A tensor that crosses the partition, as known before the computation starts.
+ * dims[i] == -1: unknown until run time (the rank is always known, section 3.3). */
+typedef struct {
+    uint32_t tensor_id;             /* caller's id, unique within a plan */
+    uint32_t dtype;                 /* RDEV_U8 ... RDEV_F64 */
+    uint32_t ndims;                 /* 0 .. RDEV_MAX_DIMS; 0 = scalar */
+    uint32_t dst_arena;             /* receiver arena id from rdev_register_arena */
+    int64_t  dims[RDEV_MAX_DIMS];
+} rdev_tensor_desc;
+
+/* Where the planner put a tensor.  Offsets are bytes from the arena base.
+ * static : payload at data_offset (bytes long), completion flag (uint32) at flag_offset.
+ * dynamic: 128-byte metadata slot at meta_offset; flag_offset is its last word
+ *          (the metadata flag); the word before it is the payload-complete flag. */
+typedef struct {
+    uint32_t tensor_id, kind, dst_arena, _pad;
+    uint64_t data_offset, bytes, flag_offset, meta_offset, region_bytes;
+} rdev_placement;
+
+typedef struct {
+    uint64_t align;             /* region alignment, power of two >= 16; 0 = RDEV_DEFAULT_ALIGN */
+    uint64_t max_static_bytes;  /* known-size tensors larger than this are sent dynamically; 0 = no limit */
+    uint64_t dyn_heap_bytes;    /* dynamic heap reserved after the regions of every destination arena */
+    uint64_t chunk_bytes;       /* large tensors are cut into work items of this size; multiple of 256; 0 = default */
+    uint32_t small_bytes;       /* tensors up to this size are copied by one wavefront; 0 = default */
+    uint32_t flags;             /* RDEV_PLAN_* */
+} rdev_plan_opts;
+
+/* The metadata record of the dynamic path, exactly as it lies in the
+ * receiver's slot (section 3.3: number of dims, size of each dim, element
+ * type, address of the sender-side tensor).  Little endian, 128 bytes.  The
+ * sender address is (src_arena, src_offset): a one-sided read can only target
+ * registered memory (section 3.4).  Also used as the message header of the RPC
+ * modes. */
+typedef struct {
+    uint32_t ndims;                 /*   0 */
+    uint32_t dtype;                 /*   4 */
+    uint64_t bytes;                 /*   8 */
+    uint64_t src_offset;            /*  16 */
+    int64_t  dims[RDEV_MAX_DIMS];   /*  24, unused = 0 */
+    uint64_t dst_offset;            /*  88, filled by the receiver when it allocates */
+    uint32_t src_arena;             /*  96 */
+    uint32_t tensor_id;             /* 100 */
+    uint32_t seq;                   /* 104 */
+    uint32_t reserved[3];           /* 108 */
+    uint32_t data_flag;             /* 120, payload complete */
+    uint32_t meta_flag;             /* 124, metadata complete: the flag at the tail of the record */
+} rdev_meta;
+
+/* One entry of an explicit batch. */
+typedef struct {
+    uint32_t    tensor_id;
+    uint32_t    ndims;              /* dynamic tensors: run-time rank (must equal the planned rank) */
+    const void *src;                /* device pointer inside a registered arena; NULL = the bound source (static only) */
+    uint32_t    dtype;              /* dynamic tensors: run-time element type (must equal the planned one) */
+    uint32_t    _pad;
+    int64_t     dims[RDEV_MAX_DIMS];/* dynamic tensors: run-time dims, all >= 0 */
+} rdev_xfer;
+
+/* ---- device (section 3.1) ------------------------------------------------ */
+
+/* Open the device on HIP device `hip_device`.  RDEV_HOST_ONLY gives a device
+ * without a GPU on which arenas, regions and plans (layout only) work and every
+ * transfer returns RDEV_E_HIP.  *out is owned by the library until rdev_close. */
+rdev_status rdev_open(rdev_device_t **out, int hip_device);
+/* Frees the device.  Plans must have been freed before (else RDEV_E_BUSY). */
+rdev_status rdev_close(rdev_device_t *dev);
+/* Last error text of the calling thread (never NULL; host pointer, valid until the next call). */
+const char *rdev_last_error(void);
+/* sizeof the ABI structs, for bindings to check: desc, placement, opts, meta, xfer, region. */
+void rdev_abi_sizes(uint32_t out[6]);
+
+/* Register caller-owned memory as an arena (section 3.4: one large buffer
+ * registered once, sub-allocated afterwards).  base: device pointer, 256-byte
+ * aligned (NULL is allowed on a host-only device).  arena_flags: 0.
+ * Arena ids count up from 0 in registration order. */
+rdev_status rdev_register_arena(rdev_device_t *dev, void *base, uint64_t bytes,
+                                uint32_t arena_flags, uint32_t *arena_id_out);
+
+/* Allocate / free a region inside an arena (section 3.1).  First fit from the
+ * lowest address; align must be a power of two; bytes > 0.  rdev_free_region
+ * takes exactly a region returned by rdev_alloc_region. */
+rdev_status rdev_alloc_region(rdev_device_t *dev, uint32_t arena_id, uint64_t bytes,
+                              uint64_t align, rdev_region *out);
+rdev_status rdev_free_region(rdev_device_t *dev, const rdev_region *region);
+
+/* ---- static planner (sections 3.2 - 3.4) --------------------------------- */
+
+/* Classify each tensor (static iff every dim is known and bytes <=
+ * max_static_bytes), reserve one block per destination arena from that arena's
+ * sub-allocator and place, in input order: for a static tensor a region
+ * [payload | pad to 16 | flag word | pad to align]; for a dynamic tensor a
+ * 128-byte metadata slot padded to align; then the arena's dynamic heap.
+ * On a GPU device the flag words and metadata slots are cleared (synchronously).
+ * t: host pointer to n descriptors.  opts: host pointer or NULL for defaults.
+ * On failure nothing stays allocated. */
+rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
+                      const rdev_plan_opts *opts, rdev_plan_t **plan_out);
+rdev_status rdev_plan_count(const rdev_plan_t *plan, uint32_t *n_out);
+/* i-th placement in input order. */
+rdev_status rdev_plan_get(const rdev_plan_t *plan, uint32_t i, rdev_placement *out);
+/* Per destination arena: offset of the plan's block, bytes of regions+slots,
+ * offset and size of the dynamic heap.  Any out pointer may be NULL. */
+rdev_status rdev_plan_arena_info(const rdev_plan_t *plan, uint32_t arena_id, uint64_t *base,
+                                 uint64_t *static_bytes, uint64_t *heap_offset, uint64_t *heap_bytes);
+/* Hand-off (section 3.4: destination addresses become properties of the sender
+ * nodes): bind the source of the i-th tensor to src_ptrs[i] (device pointers
+ * inside registered arenas; NULL entries = not bound; entries of dynamic tensors
+ * are ignored) and build + upload the descriptor table that rdev_write_batch
+ * walks.  Source ranges must not overlap their destination. */
+rdev_status rdev_plan_bind_sources(rdev_plan_t *plan, const void *const *src_ptrs, uint32_t n);
+/* Buffers for the copying modes: send_buf is the message / staging buffer,
+ * recv_buf the second buffer of RDEV_RPC3 (may be NULL otherwise).  Regions
+ * from rdev_alloc_region, 256-byte aligned. */
+rdev_status rdev_plan_bind_buffers(rdev_plan_t *plan, const rdev_region *send_buf, const rdev_region *recv_buf);
+/* Start of an iteration on the receiver: every dynamic heap of the plan is empty again. */
+rdev_status rdev_dyn_reset(rdev_plan_t *plan);
+/* Frees the plan, its tables and its blocks in the arenas. */
+rdev_status rdev_plan_free(rdev_plan_t *plan);
+
+/* ---- transfer (sections 3.2, 3.3) ---------------------------------------- */
+
+/* One-sided batched write, sender side.
+ *   x == NULL, n == 0 : every static tensor of the plan from its bound source
+ *                       (one kernel over the resident descriptor table).
+ *   otherwise         : the n listed tensors, in order.  A static tensor's
+ *                       payload is written to its region, then its flag = seq.
+ *                       For a dynamic tensor the metadata record is written
+ *                       into the receiver's slot, then the metadata flag = seq;
+ *                       the payload stays where it is until the receiver pulls.
+ * mode != RDEV_ZEROCOPY applies to static tensors only and needs
+ * rdev_plan_bind_buffers.  seq >= 1 is the value stored into the flags.
+ * The whole batch is validated before anything is enqueued. */
+rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
+                             uint32_t mode, uint32_t seq, void *stream);
+
+/* One-sided batched read, receiver side: local region <- remote tensor.
+ * Dynamic tensor (section 3.3): its metadata must have been seen by
+ * rdev_poll(..., RDEV_POLL_META); storage of round_up(bytes, align) is taken
+ * from the arena's dynamic heap in batch order, the chosen offset is recorded
+ * in the slot, the payload is copied from the sender's address, then the
+ * payload-complete flag = seq.  x[i].src/dims are ignored for dynamic tensors.
+ * Static tensor: pulled into its region exactly as rdev_write_batch would push it. */
+rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
+                            uint32_t seq, void *stream);
+
+/* Non-blocking completion test (section 3.2: the receiver polls the flag,
+ * clears it, then lets dependants run).  Reads the pinned host word that the
+ * kernel stores with system-scope release after the in-arena flag, so no GPU
+ * work is issued for a test (section 3.5: poll on the CPU side).
+ *   static tensor : ready when its flag != 0.
+ *   dynamic tensor: RDEV_POLL_META tests the metadata flag (and remembers the
+ *                   record for rdev_read_batch); otherwise the payload-complete flag.
+ *   RDEV_ALL_TENSORS: ready when every static tensor of the plan is.
+ * RDEV_POLL_CONSUME clears the flag on success: the host word at once, the
+ * in-arena word by a small kernel enqueued on `stream`.
+ * RDEV_POLL_ARENA reads the in-arena word with a synchronous copy instead (slow; for checks).
+ * meta_out (host pointer, may be NULL): dynamic tensors - the record as last
+ * delivered; static tensors after an RPC-mode delivery - dst_offset of the fresh allocation. */
+rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
+                      uint32_t poll_flags, rdev_meta *meta_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RDEV_H */

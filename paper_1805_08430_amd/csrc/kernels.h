@@ -1,0 +1,203 @@
+// Device code of the transfer path (gfx950).  Pure data movement: 16-byte
+// vector loads/stores, one vector per lane per step, no LDS and no matrix
+// cores.  Completion flags are stored by a separate small kernel that is
+// enqueued behind the copy on the same stream, so the kernel boundary is the
+// release point (paper section 3.2 needs "flag visible only after the whole
+// tensor"; a NIC gets that from ascending-address writes, a GPU does not).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rdev.h"
+
+namespace rdev {
+
+constexpr uint32_t kBlockThreads = 1024;     // 16 wavefronts
+constexpr uint32_t kWavesPerBlock = kBlockThreads / 64;
+constexpr uint32_t kInlineMax = 8;           // explicit transfers per inline launch
+constexpr uint32_t kMetaInlineMax = 4;       // metadata records per launch (kernel-argument space)
+
+// One unit of copy work.  n_sub == 0: the whole block copies (src, dst, bytes).
+// n_sub > 0: wavefront w < n_sub copies sub-item [sub_first + w] (small tensors).
+struct Item {
+    const uint8_t *src;
+    uint8_t *dst;           // always 16-byte aligned
+    uint32_t bytes;
+    uint32_t n_sub;
+    uint32_t sub_first;
+    uint32_t tensor;        // index in plan order (diagnostics only)
+};
+static_assert(sizeof(Item) == 32, "Item is 32 bytes");
+
+struct FlagEnt {
+    uint32_t *arena_flag;   // flag word inside the receiver arena
+    uint32_t mirror_idx;    // index of its host-visible word
+    uint32_t _pad;
+};
+static_assert(sizeof(FlagEnt) == 16, "FlagEnt is 16 bytes");
+
+struct InlineEnt {
+    const uint8_t *src;
+    uint8_t *dst;
+    uint64_t bytes;
+    uint32_t first_block;
+    uint32_t _pad;
+};
+struct InlineBatch {
+    InlineEnt e[kInlineMax];
+    uint32_t n;
+    uint32_t chunk;
+};
+
+struct InlineFlags {
+    uint32_t *arena_flag[kInlineMax];
+    uint32_t mirror_idx[kInlineMax];
+    uint32_t n;
+    uint32_t value;
+};
+
+struct MetaBatch {
+    uint32_t words[kMetaInlineMax][30];     // the first 120 bytes of each record
+    uint8_t *slot[kMetaInlineMax];          // receiver slot in the arena
+    uint32_t meta_idx[kMetaInlineMax];      // index of the host-visible copy of the record
+    uint32_t flag_idx[kMetaInlineMax];      // index of the host-visible metadata flag
+    uint32_t n;
+    uint32_t seq;
+};
+
+struct PostBatch {                           // after a pull: record the offset, raise payload-complete
+    uint8_t *slot[kInlineMax];
+    uint64_t dst_offset[kInlineMax];
+    uint32_t meta_idx[kInlineMax];
+    uint32_t flag_idx[kInlineMax];
+    uint32_t n;
+    uint32_t seq;
+};
+
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef v4u v4u_a4 __attribute__((aligned(4)));   // a 16-byte vector at a 4-byte aligned address
+
+__device__ __forceinline__ uint32_t funnel(uint32_t lo, uint32_t hi, uint32_t shift_bits) {
+    return (uint32_t)((((uint64_t)hi << 32) | lo) >> shift_bits);
+}
+
+// Copy `bytes` from src to dst with `nth` cooperating lanes, lane id `tid`.
+// dst is 16-byte aligned.  src may have any alignment:
+//   src % 16 == 0 : 16-byte loads
+//   src %  4 == 0 : 16-byte loads at 4-byte alignment
+//   otherwise     : five aligned dwords per vector, shifted into place; the
+//                   extra dword always shares a word with a valid source byte,
+//                   so nothing outside the source's pages is touched.
+// Streaming (non-temporal) accesses: nothing is reused.
+__device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst,
+                                          uint32_t bytes, uint32_t tid, uint32_t nth) {
+    const uint32_t nvec = bytes >> 4;
+    const uintptr_t sa = (uintptr_t)src;
+    v4u *d = (v4u *)dst;
+    if ((sa & 15) == 0) {
+        const v4u *s = (const v4u *)src;
+        for (uint32_t i = tid; i < nvec; i += nth)
+            __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
+    } else if ((sa & 3) == 0) {
+        const v4u_a4 *s = (const v4u_a4 *)src;
+        for (uint32_t i = tid; i < nvec; i += nth) {
+            v4u r = s[i];
+            __builtin_nontemporal_store(r, d + i);
+        }
+    } else {
+        const uint32_t m = (uint32_t)(sa & 3);
+        const uint32_t sh = m * 8;
+        const uint32_t *base = (const uint32_t *)(sa - m);
+        for (uint32_t i = tid; i < nvec; i += nth) {
+            const uint32_t *w = base + 4 * (size_t)i;
+            v4u lo = *(const v4u_a4 *)w;
+            uint32_t w4 = w[4];
+            v4u r;
+            r.x = funnel(lo.x, lo.y, sh);
+            r.y = funnel(lo.y, lo.z, sh);
+            r.z = funnel(lo.z, lo.w, sh);
+            r.w = funnel(lo.w, w4, sh);
+            __builtin_nontemporal_store(r, d + i);
+        }
+    }
+    const uint32_t rem = bytes & 15;
+    if (tid < rem) {
+        const size_t o = (size_t)nvec * 16 + tid;
+        dst[o] = src[o];
+    }
+}
+
+// The batched transfer: block b takes items[b].
+__global__ __launch_bounds__(kBlockThreads) void copy_table_kernel(const Item *__restrict__ items,
+                                                                    const Item *__restrict__ subs) {
+    const Item it = items[blockIdx.x];
+    if (it.n_sub == 0) {
+        copy_span(it.src, it.dst, it.bytes, threadIdx.x, kBlockThreads);
+    } else {
+        const uint32_t wave = threadIdx.x >> 6;
+        if (wave < it.n_sub) {
+            const Item s = subs[it.sub_first + wave];
+            copy_span(s.src, s.dst, s.bytes, threadIdx.x & 63, 64);
+        }
+    }
+}
+
+// A few explicit transfers whose descriptors travel in the kernel arguments.
+__global__ __launch_bounds__(kBlockThreads) void copy_inline_kernel(InlineBatch b) {
+    uint32_t k = 0;
+    for (uint32_t i = 1; i < b.n; ++i)
+        if (blockIdx.x >= b.e[i].first_block) k = i;
+    const uint64_t off = (uint64_t)(blockIdx.x - b.e[k].first_block) * b.chunk;
+    const uint64_t rem = b.e[k].bytes - off;
+    const uint32_t n = rem < b.chunk ? (uint32_t)rem : b.chunk;
+    copy_span(b.e[k].src + off, b.e[k].dst + off, n, threadIdx.x, kBlockThreads);
+}
+
+// flag <- value for a table of tensors; the host-visible word (if any) after the in-arena word.
+__global__ void flag_table_kernel(const FlagEnt *__restrict__ ents, uint32_t n, uint32_t value,
+                                  uint32_t *mirror) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    if (mirror)
+        __hip_atomic_store(mirror + ents[i].mirror_idx, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__global__ void flag_inline_kernel(InlineFlags f, uint32_t *mirror) {
+    const uint32_t i = threadIdx.x;
+    if (i >= f.n) return;
+    __hip_atomic_store(f.arena_flag[i], f.value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    if (mirror)
+        __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// Dynamic path, sender side: 120 bytes of metadata into the receiver's slot
+// (and its host-visible copy), then the flag in the record's last word.
+__global__ __launch_bounds__(64) void meta_write_kernel(MetaBatch b, uint32_t *mirror_flags, rdev_meta *mirror_meta) {
+    const uint32_t k = blockIdx.x;
+    const uint32_t t = threadIdx.x;
+    uint32_t *slot = (uint32_t *)b.slot[k];
+    uint32_t *host = (uint32_t *)(mirror_meta + b.meta_idx[k]);
+    if (t < 30) {
+        const uint32_t w = b.words[k][t];
+        slot[t] = w;
+        host[t] = w;
+    }
+    __syncthreads();
+    if (t == 0) {
+        __hip_atomic_store(slot + 31, b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mirror_flags + b.flag_idx[k], b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
+// Dynamic path, receiver side, behind the pull: record where the payload went, raise payload-complete.
+__global__ void post_pull_kernel(PostBatch b, uint32_t *mirror_flags, rdev_meta *mirror_meta) {
+    const uint32_t i = threadIdx.x;
+    if (i >= b.n) return;
+    *(uint64_t *)(b.slot[i] + 88) = b.dst_offset[i];
+    mirror_meta[b.meta_idx[i]].dst_offset = b.dst_offset[i];
+    __hip_atomic_store((uint32_t *)(b.slot[i] + 120), b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(mirror_flags + b.flag_idx[i], b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+}  // namespace rdev

@@ -1,0 +1,829 @@
+// C-ABI entry points of the memory-region device (see include/rdev.h).
+// Host logic + kernel launches; the kernels are in kernels.h, the planner in planner.cpp.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "kernels.h"
+#include "planner.h"
+#include "rdev.h"
+
+using rdev::ArenaLayout;
+using rdev::FlagEnt;
+using rdev::Item;
+
+namespace {
+
+thread_local std::string g_err = "";
+
+rdev_status fail(rdev_status st, std::string msg) {
+    g_err = std::move(msg);
+    return st;
+}
+
+#define HIP_TRY(expr)                                                                      \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess) return fail(RDEV_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+#define RDEV_TRY(expr)                 \
+    do {                               \
+        rdev_status s_ = (expr);       \
+        if (s_ != RDEV_OK) return s_;  \
+    } while (0)
+
+struct Arena {
+    uint8_t *base = nullptr;
+    uint64_t bytes = 0;
+    uint32_t flags = 0;
+    rdev::RegionAllocator alloc;
+};
+
+struct SrcLoc {
+    bool bound = false;
+    uint32_t arena = 0;
+    uint64_t offset = 0;
+};
+
+constexpr uint64_t kDefaultChunk = 16384;   // one 16-byte vector per lane of a 1024-lane block
+constexpr uint32_t kDefaultSmall = 4096;    // up to this size a tensor is one wavefront's work
+
+template <typename T>
+struct DevBuf {                               // library-owned device table
+    T *ptr = nullptr;
+    size_t n = 0;
+    ~DevBuf() { reset(); }
+    void reset() {
+        if (ptr) (void)hipFree(ptr);
+        ptr = nullptr;
+        n = 0;
+    }
+    hipError_t upload(const std::vector<T> &h) {
+        reset();
+        if (h.empty()) return hipSuccess;
+        hipError_t e = hipMalloc((void **)&ptr, h.size() * sizeof(T));
+        if (e != hipSuccess) { ptr = nullptr; return e; }
+        n = h.size();
+        return hipMemcpy(ptr, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice);
+    }
+};
+
+}  // namespace
+
+struct rdev_device_s {
+    int hip_device = RDEV_HOST_ONLY;
+    std::vector<Arena> arenas;
+    int n_plans = 0;
+    bool gpu() const { return hip_device >= 0; }
+};
+
+struct rdev_plan_s {
+    rdev_device_t *dev = nullptr;
+    rdev_plan_opts opts{};
+    std::vector<rdev_tensor_desc> descs;
+    std::vector<rdev_placement> pl;
+    std::unordered_map<uint32_t, uint32_t> by_id;    // tensor_id -> index
+    std::map<uint32_t, ArenaLayout> arenas;          // destination arena -> layout
+    std::vector<rdev_region> blocks;                 // what was taken from the sub-allocators
+    std::vector<SrcLoc> src;                         // bound sources, by index
+    std::vector<int32_t> dyn_index;                  // index -> slot in the metadata mirror, -1 if static
+    uint32_t n_dyn = 0;
+    uint32_t n_static = 0;
+    bool bound_all = false;
+
+    // device tables for the "whole plan" transfer
+    DevBuf<Item> d_items, d_subs;
+    DevBuf<FlagEnt> d_flags;                         // static tensors, plan order
+    uint32_t n_blocks = 0;
+
+    // host-visible words: flags[2*i] = completion / payload-complete, flags[2*i+1] = metadata flag
+    uint32_t *h_flags = nullptr, *d_flags_view = nullptr;
+    rdev_meta *h_meta = nullptr, *d_meta_view = nullptr;
+    std::vector<rdev_meta> polled;                   // record seen by the last metadata poll
+    std::vector<uint8_t> polled_valid;
+    std::vector<uint64_t> rpc_offset;                // per index: fresh allocation of the last RPC-mode delivery
+    std::vector<uint8_t> rpc_valid;
+
+    // buffers of the copying modes
+    bool have_send = false, have_recv = false;
+    rdev_region send_buf{}, recv_buf{};
+};
+
+namespace {
+
+rdev_status arena_of(rdev_device_t *dev, uint32_t id, Arena **out) {
+    if (id >= dev->arenas.size()) return fail(RDEV_E_INVAL, "unknown arena " + std::to_string(id));
+    *out = &dev->arenas[id];
+    return RDEV_OK;
+}
+
+// which registered arena holds [p, p+bytes)?
+rdev_status locate(rdev_device_t *dev, const void *p, uint64_t bytes, SrcLoc *out) {
+    const uintptr_t a = (uintptr_t)p;
+    for (uint32_t i = 0; i < dev->arenas.size(); ++i) {
+        const Arena &ar = dev->arenas[i];
+        const uintptr_t lo = (uintptr_t)ar.base;
+        if (!ar.base || a < lo || a - lo > ar.bytes) continue;
+        if (bytes > ar.bytes - (a - lo)) continue;
+        out->bound = true;
+        out->arena = i;
+        out->offset = a - lo;
+        return RDEV_OK;
+    }
+    return fail(RDEV_E_RANGE, "address range is not inside a registered arena");
+}
+
+bool ranges_overlap(uint32_t a0, uint64_t o0, uint32_t a1, uint64_t o1, uint64_t bytes) {
+    return bytes && a0 == a1 && o0 < o1 + bytes && o1 < o0 + bytes;
+}
+
+rdev_status index_of(const rdev_plan_t *plan, uint32_t tensor_id, uint32_t *idx) {
+    auto it = plan->by_id.find(tensor_id);
+    if (it == plan->by_id.end()) return fail(RDEV_E_INVAL, "unknown tensor " + std::to_string(tensor_id));
+    *idx = it->second;
+    return RDEV_OK;
+}
+
+uint8_t *arena_ptr(rdev_plan_t *plan, uint32_t arena, uint64_t off) { return plan->dev->arenas[arena].base + off; }
+
+rdev_status launch_check(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(RDEV_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+    return RDEV_OK;
+}
+
+// cut one tensor into work items
+void cut_items(const uint8_t *src, uint8_t *dst, uint64_t bytes, uint32_t tensor, uint64_t chunk, uint32_t small,
+               std::vector<Item> &items, std::vector<Item> &subs, std::vector<Item> &pending_small) {
+    if (bytes <= small) {
+        pending_small.push_back(Item{src, dst, (uint32_t)bytes, 0, 0, tensor});
+        if (pending_small.size() == rdev::kWavesPerBlock) {
+            items.push_back(Item{nullptr, nullptr, 0, (uint32_t)pending_small.size(), (uint32_t)subs.size(), tensor});
+            subs.insert(subs.end(), pending_small.begin(), pending_small.end());
+            pending_small.clear();
+        }
+        return;
+    }
+    for (uint64_t off = 0; off < bytes; off += chunk) {
+        const uint64_t n = std::min<uint64_t>(chunk, bytes - off);
+        items.push_back(Item{src + off, dst + off, (uint32_t)n, 0, 0, tensor});
+    }
+}
+
+void flush_small(std::vector<Item> &items, std::vector<Item> &subs, std::vector<Item> &pending_small) {
+    if (pending_small.empty()) return;
+    items.push_back(Item{nullptr, nullptr, 0, (uint32_t)pending_small.size(), (uint32_t)subs.size(), 0});
+    subs.insert(subs.end(), pending_small.begin(), pending_small.end());
+    pending_small.clear();
+}
+
+rdev_status require_gpu(const rdev_device_t *dev) {
+    if (!dev->gpu()) return fail(RDEV_E_HIP, "host-only device: no GPU to run a transfer on");
+    return RDEV_OK;
+}
+
+struct ResolvedStatic {
+    uint32_t idx;
+    const uint8_t *src;
+    uint8_t *dst;
+    uint64_t bytes;
+};
+
+// validate one static transfer and resolve its addresses
+rdev_status resolve_static(rdev_plan_t *plan, uint32_t idx, const void *src_override, ResolvedStatic *out) {
+    const rdev_placement &p = plan->pl[idx];
+    SrcLoc loc;
+    if (src_override) {
+        RDEV_TRY(locate(plan->dev, src_override, p.bytes, &loc));
+    } else {
+        loc = plan->src[idx];
+        if (!loc.bound) return fail(RDEV_E_STATE, "tensor " + std::to_string(p.tensor_id) + " has no bound source");
+    }
+    if (ranges_overlap(loc.arena, loc.offset, p.dst_arena, p.data_offset, p.bytes))
+        return fail(RDEV_E_OVERLAP, "source of tensor " + std::to_string(p.tensor_id) + " overlaps its destination");
+    out->idx = idx;
+    out->src = plan->dev->arenas[loc.arena].base + loc.offset;
+    out->dst = arena_ptr(plan, p.dst_arena, p.data_offset);
+    out->bytes = p.bytes;
+    return RDEV_OK;
+}
+
+// enqueue copies for up to any number of resolved transfers, kInlineMax per launch
+rdev_status launch_inline_copies(rdev_plan_t *plan, const std::vector<ResolvedStatic> &v, hipStream_t s) {
+    const uint64_t chunk = plan->opts.chunk_bytes;
+    size_t i = 0;
+    while (i < v.size()) {
+        rdev::InlineBatch b{};
+        b.chunk = (uint32_t)chunk;
+        uint64_t blocks = 0;
+        while (i < v.size() && b.n < rdev::kInlineMax) {
+            const uint64_t nb = (v[i].bytes + chunk - 1) / chunk;
+            if (blocks + nb > 0x7fffffffull) {
+                if (b.n == 0) return fail(RDEV_E_INVAL, "transfer too large for one launch with this chunk size");
+                break;
+            }
+            if (nb) {
+                b.e[b.n] = rdev::InlineEnt{v[i].src, v[i].dst, v[i].bytes, (uint32_t)blocks, 0};
+                b.n++;
+                blocks += nb;
+            }
+            ++i;
+        }
+        if (blocks) {
+            hipLaunchKernelGGL(rdev::copy_inline_kernel, dim3((uint32_t)blocks), dim3(rdev::kBlockThreads), 0, s, b);
+            RDEV_TRY(launch_check("copy_inline_kernel"));
+        }
+    }
+    return RDEV_OK;
+}
+
+// flag words (in arena + host-visible) <- value, for a list of (arena pointer, mirror index)
+rdev_status launch_inline_flags(rdev_plan_t *plan, const std::vector<std::pair<uint32_t *, uint32_t>> &v,
+                                uint32_t value, bool with_mirror, hipStream_t s) {
+    size_t i = 0;
+    while (i < v.size()) {
+        rdev::InlineFlags f{};
+        f.value = value;
+        while (i < v.size() && f.n < rdev::kInlineMax) {
+            f.arena_flag[f.n] = v[i].first;
+            f.mirror_idx[f.n] = v[i].second;
+            f.n++;
+            ++i;
+        }
+        hipLaunchKernelGGL(rdev::flag_inline_kernel, dim3(1), dim3(64), 0, s, f,
+                           with_mirror ? plan->d_flags_view : nullptr);
+        RDEV_TRY(launch_check("flag_inline_kernel"));
+    }
+    return RDEV_OK;
+}
+
+void free_plan_blocks(rdev_plan_t *plan) {
+    std::string ignore;
+    for (const rdev_region &r : plan->blocks) plan->dev->arenas[r.arena_id].alloc.release(r.offset, r.bytes, ignore);
+    plan->blocks.clear();
+}
+
+void destroy_plan(rdev_plan_t *plan) {
+    free_plan_blocks(plan);
+    if (plan->h_flags) (void)hipHostFree(plan->h_flags);
+    if (plan->h_meta) (void)hipHostFree(plan->h_meta);
+    plan->dev->n_plans--;
+    delete plan;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *rdev_last_error(void) { return g_err.c_str(); }
+
+void rdev_abi_sizes(uint32_t out[6]) {
+    out[0] = sizeof(rdev_tensor_desc);
+    out[1] = sizeof(rdev_placement);
+    out[2] = sizeof(rdev_plan_opts);
+    out[3] = sizeof(rdev_meta);
+    out[4] = sizeof(rdev_xfer);
+    out[5] = sizeof(rdev_region);
+}
+
+rdev_status rdev_open(rdev_device_t **out, int hip_device) {
+    if (!out) return fail(RDEV_E_INVAL, "out is NULL");
+    if (hip_device < RDEV_HOST_ONLY) return fail(RDEV_E_INVAL, "bad device index");
+    if (hip_device >= 0) {
+        int n = 0;
+        HIP_TRY(hipGetDeviceCount(&n));
+        if (hip_device >= n) return fail(RDEV_E_HIP, "no such HIP device");
+        HIP_TRY(hipSetDevice(hip_device));
+    }
+    rdev_device_t *d = new rdev_device_t();
+    d->hip_device = hip_device;
+    *out = d;
+    return RDEV_OK;
+}
+
+rdev_status rdev_close(rdev_device_t *dev) {
+    if (!dev) return fail(RDEV_E_INVAL, "dev is NULL");
+    if (dev->n_plans) return fail(RDEV_E_BUSY, "plans are still alive on this device");
+    delete dev;
+    return RDEV_OK;
+}
+
+rdev_status rdev_register_arena(rdev_device_t *dev, void *base, uint64_t bytes, uint32_t arena_flags,
+                                uint32_t *arena_id_out) {
+    if (!dev || !arena_id_out) return fail(RDEV_E_INVAL, "NULL argument");
+    if (arena_flags) return fail(RDEV_E_INVAL, "unknown arena flags");
+    if (!bytes) return fail(RDEV_E_INVAL, "arena bytes must be positive");
+    if (dev->gpu() && !base) return fail(RDEV_E_INVAL, "arena base is NULL");
+    if ((uintptr_t)base & 255) return fail(RDEV_E_ALIGN, "arena base must be 256-byte aligned");
+    if (base && (uintptr_t)base + bytes < (uintptr_t)base) return fail(RDEV_E_OVERFLOW, "arena wraps the address space");
+    for (const Arena &a : dev->arenas) {
+        if (!a.base || !base) continue;
+        const uintptr_t lo = (uintptr_t)a.base, hi = lo + a.bytes, l2 = (uintptr_t)base, h2 = l2 + bytes;
+        if (l2 < hi && lo < h2) return fail(RDEV_E_OVERLAP, "arena overlaps a registered arena");
+    }
+    Arena a;
+    a.base = (uint8_t *)base;
+    a.bytes = bytes;
+    a.flags = arena_flags;
+    a.alloc = rdev::RegionAllocator(bytes);
+    dev->arenas.push_back(std::move(a));
+    *arena_id_out = (uint32_t)dev->arenas.size() - 1;
+    return RDEV_OK;
+}
+
+rdev_status rdev_alloc_region(rdev_device_t *dev, uint32_t arena_id, uint64_t bytes, uint64_t align, rdev_region *out) {
+    if (!dev || !out) return fail(RDEV_E_INVAL, "NULL argument");
+    Arena *a;
+    RDEV_TRY(arena_of(dev, arena_id, &a));
+    uint64_t off;
+    std::string err;
+    rdev_status st = a->alloc.alloc(bytes, align, &off, err);
+    if (st != RDEV_OK) return fail(st, err);
+    out->arena_id = arena_id;
+    out->_pad = 0;
+    out->offset = off;
+    out->bytes = bytes;
+    return RDEV_OK;
+}
+
+rdev_status rdev_free_region(rdev_device_t *dev, const rdev_region *region) {
+    if (!dev || !region) return fail(RDEV_E_INVAL, "NULL argument");
+    Arena *a;
+    RDEV_TRY(arena_of(dev, region->arena_id, &a));
+    std::string err;
+    rdev_status st = a->alloc.release(region->offset, region->bytes, err);
+    if (st != RDEV_OK) return fail(st, err);
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n, const rdev_plan_opts *opts,
+                      rdev_plan_t **plan_out) {
+    if (!dev || !plan_out || (!t && n)) return fail(RDEV_E_INVAL, "NULL argument");
+    rdev_plan_opts o{};
+    if (opts) o = *opts;
+    if (!o.align) o.align = RDEV_DEFAULT_ALIGN;
+    if (!o.chunk_bytes) o.chunk_bytes = kDefaultChunk;
+    if (!o.small_bytes) o.small_bytes = kDefaultSmall;
+    if (o.chunk_bytes % 256 || o.chunk_bytes > (1u << 30)) return fail(RDEV_E_INVAL, "chunk_bytes must be a multiple of 256, at most 1 GiB");
+    if (o.small_bytes > o.chunk_bytes) o.small_bytes = (uint32_t)o.chunk_bytes;
+    if (o.flags & ~(uint32_t)RDEV_PLAN_CHECK_BUSY) return fail(RDEV_E_INVAL, "unknown plan flags");
+
+    std::unique_ptr<rdev_plan_t> plan(new rdev_plan_t());
+    plan->dev = dev;
+    plan->opts = o;
+    std::string err;
+    rdev_status st = rdev::layout(t, n, o.align, o.max_static_bytes, o.dyn_heap_bytes, plan->pl, plan->arenas, err);
+    if (st != RDEV_OK) return fail(st, err);
+    for (auto &kv : plan->arenas)
+        if (kv.first >= dev->arenas.size()) return fail(RDEV_E_INVAL, "unknown arena " + std::to_string(kv.first));
+
+    // one block per destination arena from its sub-allocator (ascending arena id)
+    for (auto &kv : plan->arenas) {
+        ArenaLayout &al = kv.second;
+        if (!al.total()) continue;
+        uint64_t base;
+        st = dev->arenas[kv.first].alloc.alloc(al.total(), o.align, &base, err);
+        if (st != RDEV_OK) {
+            free_plan_blocks(plan.get());
+            return fail(st, "arena " + std::to_string(kv.first) + ": " + err);
+        }
+        plan->blocks.push_back(rdev_region{kv.first, 0, base, al.total()});
+        al.base = base;
+        al.heap_offset += base;
+    }
+    plan->descs.assign(t, t + n);
+    plan->src.resize(n);
+    plan->dyn_index.assign(n, -1);
+    plan->rpc_offset.assign(n, 0);
+    plan->rpc_valid.assign(n, 0);
+    for (uint32_t i = 0; i < n; ++i) {
+        rdev_placement &p = plan->pl[i];
+        const uint64_t b = plan->arenas[p.dst_arena].base;
+        if (p.kind == RDEV_STATIC) { p.data_offset += b; plan->n_static++; }
+        else { p.meta_offset += b; plan->dyn_index[i] = (int32_t)plan->n_dyn++; }
+        p.flag_offset += b;
+        plan->by_id[p.tensor_id] = i;
+    }
+    plan->polled.resize(plan->n_dyn);
+    plan->polled_valid.assign(plan->n_dyn, 0);
+
+    dev->n_plans++;              // from here on destroy_plan() undoes everything
+    rdev_plan_t *raw = plan.release();
+    if (dev->gpu()) {
+        auto bail = [&](hipError_t e, const char *what) {
+            destroy_plan(raw);
+            return fail(RDEV_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+        };
+        hipError_t e = hipSetDevice(dev->hip_device);
+        if (e != hipSuccess) return bail(e, "hipSetDevice");
+        const size_t nflags = std::max<size_t>(2 * (size_t)n, 2);
+        e = hipHostMalloc((void **)&raw->h_flags, nflags * sizeof(uint32_t), hipHostMallocMapped | hipHostMallocCoherent);
+        if (e != hipSuccess) { raw->h_flags = nullptr; return bail(e, "hipHostMalloc(flags)"); }
+        std::memset(raw->h_flags, 0, nflags * sizeof(uint32_t));
+        e = hipHostGetDevicePointer((void **)&raw->d_flags_view, raw->h_flags, 0);
+        if (e != hipSuccess) return bail(e, "hipHostGetDevicePointer(flags)");
+        const size_t nmeta = std::max<size_t>(raw->n_dyn, 1);
+        e = hipHostMalloc((void **)&raw->h_meta, nmeta * sizeof(rdev_meta), hipHostMallocMapped | hipHostMallocCoherent);
+        if (e != hipSuccess) { raw->h_meta = nullptr; return bail(e, "hipHostMalloc(meta)"); }
+        std::memset(raw->h_meta, 0, nmeta * sizeof(rdev_meta));
+        e = hipHostGetDevicePointer((void **)&raw->d_meta_view, raw->h_meta, 0);
+        if (e != hipSuccess) return bail(e, "hipHostGetDevicePointer(meta)");
+
+        // flag table of the static tensors; clear every flag word and metadata slot
+        std::vector<FlagEnt> fe;
+        for (uint32_t i = 0; i < n; ++i) {
+            const rdev_placement &p = raw->pl[i];
+            if (p.kind == RDEV_STATIC) {
+                fe.push_back(FlagEnt{(uint32_t *)arena_ptr(raw, p.dst_arena, p.flag_offset), 2 * i, 0});
+            } else {
+                e = hipMemset(arena_ptr(raw, p.dst_arena, p.meta_offset), 0, RDEV_META_BYTES);
+                if (e != hipSuccess) return bail(e, "hipMemset(metadata slot)");
+            }
+        }
+        e = raw->d_flags.upload(fe);
+        if (e != hipSuccess) return bail(e, "upload(flag table)");
+        if (!fe.empty()) {
+            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(((uint32_t)fe.size() + 255) / 256), dim3(256), 0, 0,
+                               raw->d_flags.ptr, (uint32_t)fe.size(), 0u, (uint32_t *)nullptr);
+            e = hipGetLastError();
+            if (e != hipSuccess) return bail(e, "flag_table_kernel");
+        }
+        e = hipDeviceSynchronize();
+        if (e != hipSuccess) return bail(e, "hipDeviceSynchronize");
+    }
+    *plan_out = raw;
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan_count(const rdev_plan_t *plan, uint32_t *n_out) {
+    if (!plan || !n_out) return fail(RDEV_E_INVAL, "NULL argument");
+    *n_out = (uint32_t)plan->pl.size();
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan_get(const rdev_plan_t *plan, uint32_t i, rdev_placement *out) {
+    if (!plan || !out) return fail(RDEV_E_INVAL, "NULL argument");
+    if (i >= plan->pl.size()) return fail(RDEV_E_INVAL, "placement index out of range");
+    *out = plan->pl[i];
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan_arena_info(const rdev_plan_t *plan, uint32_t arena_id, uint64_t *base, uint64_t *static_bytes,
+                                 uint64_t *heap_offset, uint64_t *heap_bytes) {
+    if (!plan) return fail(RDEV_E_INVAL, "NULL argument");
+    auto it = plan->arenas.find(arena_id);
+    if (it == plan->arenas.end()) return fail(RDEV_E_INVAL, "arena is not a destination of this plan");
+    if (base) *base = it->second.base;
+    if (static_bytes) *static_bytes = it->second.static_bytes;
+    if (heap_offset) *heap_offset = it->second.heap_offset;
+    if (heap_bytes) *heap_bytes = it->second.heap_bytes;
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan_bind_sources(rdev_plan_t *plan, const void *const *src_ptrs, uint32_t n) {
+    if (!plan || (!src_ptrs && n)) return fail(RDEV_E_INVAL, "NULL argument");
+    if (n != plan->pl.size()) return fail(RDEV_E_INVAL, "need one source pointer per planned tensor");
+    std::vector<SrcLoc> locs(n);
+    bool all = true;
+    for (uint32_t i = 0; i < n; ++i) {
+        const rdev_placement &p = plan->pl[i];
+        if (p.kind != RDEV_STATIC) continue;
+        if (!src_ptrs[i]) { all = false; continue; }
+        if (plan->dev->gpu() || plan->dev->arenas.size()) {
+            RDEV_TRY(locate(plan->dev, src_ptrs[i], p.bytes, &locs[i]));
+        }
+        if (ranges_overlap(locs[i].arena, locs[i].offset, p.dst_arena, p.data_offset, p.bytes))
+            return fail(RDEV_E_OVERLAP, "source of tensor " + std::to_string(p.tensor_id) + " overlaps its destination");
+    }
+    // descriptor table (section 3.4: the sender keeps each destination address with the sending node)
+    std::vector<Item> items, subs, pending;
+    for (uint32_t i = 0; i < n; ++i) {
+        const rdev_placement &p = plan->pl[i];
+        if (p.kind != RDEV_STATIC || !locs[i].bound) continue;
+        const uint8_t *s = plan->dev->arenas[locs[i].arena].base + locs[i].offset;
+        cut_items(s, arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, i, plan->opts.chunk_bytes,
+                  plan->opts.small_bytes, items, subs, pending);
+    }
+    flush_small(items, subs, pending);
+    if (items.size() > 0x7fffffffull) return fail(RDEV_E_INVAL, "too many work items for one launch; raise chunk_bytes");
+    if (plan->dev->gpu()) {
+        HIP_TRY(hipSetDevice(plan->dev->hip_device));
+        HIP_TRY(hipDeviceSynchronize());          // nothing may still read the old tables
+        HIP_TRY(plan->d_items.upload(items));
+        HIP_TRY(plan->d_subs.upload(subs));
+    }
+    plan->n_blocks = (uint32_t)items.size();
+    plan->src = std::move(locs);
+    plan->bound_all = all;
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan_bind_buffers(rdev_plan_t *plan, const rdev_region *send_buf, const rdev_region *recv_buf) {
+    if (!plan || !send_buf) return fail(RDEV_E_INVAL, "NULL argument");
+    for (const rdev_region *r : {send_buf, recv_buf}) {
+        if (!r) continue;
+        Arena *a;
+        RDEV_TRY(arena_of(plan->dev, r->arena_id, &a));
+        if (r->offset % 256) return fail(RDEV_E_ALIGN, "buffer must be 256-byte aligned");
+        if (r->offset > a->bytes || r->bytes > a->bytes - r->offset) return fail(RDEV_E_RANGE, "buffer outside its arena");
+    }
+    plan->send_buf = *send_buf;
+    plan->have_send = true;
+    plan->have_recv = recv_buf != nullptr;
+    if (recv_buf) plan->recv_buf = *recv_buf;
+    return RDEV_OK;
+}
+
+rdev_status rdev_dyn_reset(rdev_plan_t *plan) {
+    if (!plan) return fail(RDEV_E_INVAL, "NULL argument");
+    for (auto &kv : plan->arenas) kv.second.heap_ptr = 0;
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan_free(rdev_plan_t *plan) {
+    if (!plan) return fail(RDEV_E_INVAL, "NULL argument");
+    if (plan->dev->gpu()) {
+        HIP_TRY(hipSetDevice(plan->dev->hip_device));
+        HIP_TRY(hipDeviceSynchronize());          // kernels may still read the tables
+    }
+    destroy_plan(plan);
+    return RDEV_OK;
+}
+
+static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t s) {
+    if (!plan->bound_all) return fail(RDEV_E_STATE, "not every static tensor has a bound source");
+    if (plan->opts.flags & RDEV_PLAN_CHECK_BUSY) {
+        for (uint32_t i = 0; i < plan->pl.size(); ++i)
+            if (plan->pl[i].kind == RDEV_STATIC && __atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE))
+                return fail(RDEV_E_BUSY, "tensor " + std::to_string(plan->pl[i].tensor_id) + " has not been consumed");
+    }
+    if (plan->n_blocks) {
+        hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_blocks), dim3(rdev::kBlockThreads), 0, s,
+                           plan->d_items.ptr, plan->d_subs.ptr);
+        RDEV_TRY(launch_check("copy_table_kernel"));
+    }
+    if (plan->n_static) {
+        hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
+                           plan->d_flags.ptr, plan->n_static, seq, plan->d_flags_view);
+        RDEV_TRY(launch_check("flag_table_kernel"));
+    }
+    return RDEV_OK;
+}
+
+// static tensors listed explicitly (write or pull: on one GPU the same movement)
+static rdev_status transfer_static_list(rdev_plan_t *plan, const std::vector<std::pair<uint32_t, const void *>> &list,
+                                        uint32_t seq, hipStream_t s) {
+    std::vector<ResolvedStatic> v(list.size());
+    std::vector<std::pair<uint32_t *, uint32_t>> flags;
+    for (size_t k = 0; k < list.size(); ++k) {
+        RDEV_TRY(resolve_static(plan, list[k].first, list[k].second, &v[k]));
+        const rdev_placement &p = plan->pl[list[k].first];
+        if ((plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && __atomic_load_n(&plan->h_flags[2 * list[k].first], __ATOMIC_ACQUIRE))
+            return fail(RDEV_E_BUSY, "tensor " + std::to_string(p.tensor_id) + " has not been consumed");
+        flags.emplace_back((uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset), 2 * list[k].first);
+    }
+    RDEV_TRY(launch_inline_copies(plan, v, s));
+    return launch_inline_flags(plan, flags, seq, true, s);
+}
+
+rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n, uint32_t mode,
+                             uint32_t seq, void *stream) {
+    if (!dev || !plan || plan->dev != dev) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
+    if ((x == nullptr) != (n == 0)) return fail(RDEV_E_INVAL, "x and n must both be empty or both be given");
+    if (!seq) return fail(RDEV_E_INVAL, "seq must be >= 1");
+    if (mode > RDEV_SENDERCOPY) return fail(RDEV_E_INVAL, "unknown mode");
+    RDEV_TRY(require_gpu(dev));
+    hipStream_t s = (hipStream_t)stream;
+    if (mode != RDEV_ZEROCOPY) return fail(RDEV_E_INVAL, "copying modes are not built in this version");
+    if (!x) return write_static_all(plan, seq, s);
+
+    // validate the whole batch first
+    std::vector<std::pair<uint32_t, const void *>> statics;
+    struct Dyn { uint32_t idx; SrcLoc loc; uint64_t bytes; const rdev_xfer *x; };
+    std::vector<Dyn> dyns;
+    for (uint32_t k = 0; k < n; ++k) {
+        uint32_t idx;
+        RDEV_TRY(index_of(plan, x[k].tensor_id, &idx));
+        const rdev_placement &p = plan->pl[idx];
+        if (p.kind == RDEV_STATIC) {
+            statics.emplace_back(idx, x[k].src);
+            continue;
+        }
+        const rdev_tensor_desc &d = plan->descs[idx];
+        if (x[k].ndims != d.ndims) return fail(RDEV_E_INVAL, "run-time rank differs from the planned rank");
+        if (x[k].dtype != d.dtype) return fail(RDEV_E_INVAL, "run-time element type differs from the planned one");
+        for (uint32_t j = 0; j < d.ndims; ++j)
+            if (d.dims[j] >= 0 && x[k].dims[j] != d.dims[j]) return fail(RDEV_E_INVAL, "a dim known at plan time changed");
+        uint64_t nb;
+        std::string err;
+        rdev_status st = rdev::tensor_bytes(x[k].dtype, x[k].ndims, x[k].dims, &nb, err);
+        if (st != RDEV_OK) return fail(st, err);
+        if (!x[k].src) return fail(RDEV_E_INVAL, "a dynamic tensor needs a source address");
+        Dyn dy{idx, {}, nb, &x[k]};
+        RDEV_TRY(locate(dev, x[k].src, nb, &dy.loc));
+        if ((plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && __atomic_load_n(&plan->h_flags[2 * idx + 1], __ATOMIC_ACQUIRE))
+            return fail(RDEV_E_BUSY, "metadata of tensor " + std::to_string(p.tensor_id) + " has not been consumed");
+        dyns.push_back(dy);
+    }
+    // enqueue in batch order: runs of static tensors, runs of dynamic ones
+    // (order inside the stream equals batch order because each group is launched when met)
+    size_t si = 0, di = 0;
+    uint32_t k = 0;
+    while (k < n) {
+        uint32_t idx = plan->by_id[x[k].tensor_id];
+        if (plan->pl[idx].kind == RDEV_STATIC) {
+            std::vector<std::pair<uint32_t, const void *>> run;
+            while (k < n && plan->pl[plan->by_id[x[k].tensor_id]].kind == RDEV_STATIC) { run.push_back(statics[si++]); ++k; }
+            RDEV_TRY(transfer_static_list(plan, run, seq, s));
+        } else {
+            while (k < n && plan->pl[plan->by_id[x[k].tensor_id]].kind == RDEV_DYNAMIC) {
+                rdev::MetaBatch mb{};
+                mb.seq = seq;
+                while (k < n && mb.n < rdev::kMetaInlineMax && plan->pl[plan->by_id[x[k].tensor_id]].kind == RDEV_DYNAMIC) {
+                    const Dyn &dy = dyns[di++];
+                    const rdev_placement &p = plan->pl[dy.idx];
+                    rdev_meta rec{};
+                    rec.ndims = dy.x->ndims;
+                    rec.dtype = dy.x->dtype;
+                    rec.bytes = dy.bytes;
+                    rec.src_offset = dy.loc.offset;
+                    for (uint32_t j = 0; j < dy.x->ndims; ++j) rec.dims[j] = dy.x->dims[j];
+                    rec.src_arena = dy.loc.arena;
+                    rec.tensor_id = p.tensor_id;
+                    rec.seq = seq;
+                    std::memcpy(mb.words[mb.n], &rec, 120);
+                    mb.slot[mb.n] = arena_ptr(plan, p.dst_arena, p.meta_offset);
+                    mb.meta_idx[mb.n] = (uint32_t)plan->dyn_index[dy.idx];
+                    mb.flag_idx[mb.n] = 2 * dy.idx + 1;
+                    mb.n++;
+                    ++k;
+                }
+                hipLaunchKernelGGL(rdev::meta_write_kernel, dim3(mb.n), dim3(64), 0, s, mb, plan->d_flags_view,
+                                   plan->d_meta_view);
+                RDEV_TRY(launch_check("meta_write_kernel"));
+            }
+        }
+    }
+    return RDEV_OK;
+}
+
+rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n, uint32_t seq,
+                            void *stream) {
+    if (!dev || !plan || plan->dev != dev) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
+    if ((x == nullptr) != (n == 0)) return fail(RDEV_E_INVAL, "x and n must both be empty or both be given");
+    if (!seq) return fail(RDEV_E_INVAL, "seq must be >= 1");
+    RDEV_TRY(require_gpu(dev));
+    hipStream_t s = (hipStream_t)stream;
+    if (!x) return write_static_all(plan, seq, s);
+
+    // validate; heap space is claimed for the batch only if all of it fits
+    std::map<uint32_t, uint64_t> heap_ptr;
+    for (auto &kv : plan->arenas) heap_ptr[kv.first] = kv.second.heap_ptr;
+    struct Pull { uint32_t idx; ResolvedStatic r; uint64_t dst_offset; };
+    std::vector<Pull> pulls;
+    std::vector<std::pair<uint32_t, const void *>> statics;
+    for (uint32_t k = 0; k < n; ++k) {
+        uint32_t idx;
+        RDEV_TRY(index_of(plan, x[k].tensor_id, &idx));
+        const rdev_placement &p = plan->pl[idx];
+        if (p.kind == RDEV_STATIC) {
+            ResolvedStatic r;
+            RDEV_TRY(resolve_static(plan, idx, x[k].src, &r));
+            continue;
+        }
+        const int32_t di = plan->dyn_index[idx];
+        if (!plan->polled_valid[di]) return fail(RDEV_E_STATE, "metadata of tensor " + std::to_string(p.tensor_id) + " has not been polled");
+        const rdev_meta &m = plan->polled[di];
+        Arena *sa;
+        RDEV_TRY(arena_of(dev, m.src_arena, &sa));
+        if (m.src_offset > sa->bytes || m.bytes > sa->bytes - m.src_offset) return fail(RDEV_E_RANGE, "sender address outside its arena");
+        const ArenaLayout &al = plan->arenas[p.dst_arena];
+        uint64_t need;
+        if (!rdev::round_up_checked(m.bytes, plan->opts.align, &need) || heap_ptr[p.dst_arena] + need < need ||
+            heap_ptr[p.dst_arena] + need > al.heap_bytes)
+            return fail(RDEV_E_NOMEM, "dynamic heap of arena " + std::to_string(p.dst_arena) + " exhausted");
+        Pull pu;
+        pu.idx = idx;
+        pu.dst_offset = al.heap_offset + heap_ptr[p.dst_arena];
+        heap_ptr[p.dst_arena] += need;
+        if (ranges_overlap(m.src_arena, m.src_offset, p.dst_arena, pu.dst_offset, m.bytes))
+            return fail(RDEV_E_OVERLAP, "sender tensor overlaps the receiver's fresh allocation");
+        pu.r = ResolvedStatic{idx, sa->base + m.src_offset, arena_ptr(plan, p.dst_arena, pu.dst_offset), m.bytes};
+        pulls.push_back(pu);
+    }
+    // commit
+    for (auto &kv : plan->arenas) kv.second.heap_ptr = heap_ptr[kv.first];
+    size_t pi = 0;
+    uint32_t k = 0;
+    while (k < n) {
+        if (plan->pl[plan->by_id[x[k].tensor_id]].kind == RDEV_STATIC) {
+            std::vector<std::pair<uint32_t, const void *>> run;
+            while (k < n && plan->pl[plan->by_id[x[k].tensor_id]].kind == RDEV_STATIC) {
+                run.emplace_back(plan->by_id[x[k].tensor_id], x[k].src);
+                ++k;
+            }
+            RDEV_TRY(transfer_static_list(plan, run, seq, s));
+            continue;
+        }
+        std::vector<ResolvedStatic> copies;
+        rdev::PostBatch pb{};
+        pb.seq = seq;
+        while (k < n && pb.n < rdev::kInlineMax && plan->pl[plan->by_id[x[k].tensor_id]].kind == RDEV_DYNAMIC) {
+            const Pull &pu = pulls[pi++];
+            const rdev_placement &p = plan->pl[pu.idx];
+            copies.push_back(pu.r);
+            pb.slot[pb.n] = arena_ptr(plan, p.dst_arena, p.meta_offset);
+            pb.dst_offset[pb.n] = pu.dst_offset;
+            pb.meta_idx[pb.n] = (uint32_t)plan->dyn_index[pu.idx];
+            pb.flag_idx[pb.n] = 2 * pu.idx;
+            pb.n++;
+            plan->polled_valid[plan->dyn_index[pu.idx]] = 0;
+            ++k;
+        }
+        RDEV_TRY(launch_inline_copies(plan, copies, s));
+        hipLaunchKernelGGL(rdev::post_pull_kernel, dim3(1), dim3(64), 0, s, pb, plan->d_flags_view, plan->d_meta_view);
+        RDEV_TRY(launch_check("post_pull_kernel"));
+    }
+    return RDEV_OK;
+}
+
+rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id, uint32_t poll_flags, rdev_meta *meta_out,
+                      void *stream) {
+    if (!dev || !plan || plan->dev != dev) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
+    if (poll_flags & ~(uint32_t)(RDEV_POLL_CONSUME | RDEV_POLL_META | RDEV_POLL_ARENA)) return fail(RDEV_E_INVAL, "unknown poll flags");
+    RDEV_TRY(require_gpu(dev));
+    hipStream_t s = (hipStream_t)stream;
+    const bool consume = poll_flags & RDEV_POLL_CONSUME;
+
+    if (tensor_id == RDEV_ALL_TENSORS) {
+        if (poll_flags & (RDEV_POLL_META | RDEV_POLL_ARENA)) return fail(RDEV_E_INVAL, "RDEV_ALL_TENSORS polls host-visible static flags only");
+        for (uint32_t i = 0; i < plan->pl.size(); ++i)
+            if (plan->pl[i].kind == RDEV_STATIC && !__atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE)) return RDEV_NOT_READY;
+        if (consume && plan->n_static) {
+            for (uint32_t i = 0; i < plan->pl.size(); ++i)
+                if (plan->pl[i].kind == RDEV_STATIC) __atomic_store_n(&plan->h_flags[2 * i], 0u, __ATOMIC_RELEASE);
+            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
+                               plan->d_flags.ptr, plan->n_static, 0u, (uint32_t *)nullptr);
+            RDEV_TRY(launch_check("flag_table_kernel"));
+        }
+        return RDEV_OK;
+    }
+
+    uint32_t idx;
+    RDEV_TRY(index_of(plan, tensor_id, &idx));
+    const rdev_placement &p = plan->pl[idx];
+    const bool dyn = p.kind == RDEV_DYNAMIC;
+    if ((poll_flags & RDEV_POLL_META) && !dyn) return fail(RDEV_E_INVAL, "RDEV_POLL_META on a static tensor");
+    const bool want_meta = dyn && (poll_flags & RDEV_POLL_META);
+    const uint32_t widx = 2 * idx + (want_meta ? 1 : 0);
+    uint32_t *arena_flag = (uint32_t *)arena_ptr(plan, p.dst_arena, dyn ? p.meta_offset + (want_meta ? 124 : 120) : p.flag_offset);
+
+    uint32_t v;
+    if (poll_flags & RDEV_POLL_ARENA) {
+        HIP_TRY(hipMemcpy(&v, arena_flag, sizeof(v), hipMemcpyDeviceToHost));
+    } else {
+        v = __atomic_load_n(&plan->h_flags[widx], __ATOMIC_ACQUIRE);
+    }
+    if (!v) return RDEV_NOT_READY;
+
+    if (dyn) {
+        rdev_meta rec;
+        if (poll_flags & RDEV_POLL_ARENA) {
+            HIP_TRY(hipMemcpy(&rec, arena_ptr(plan, p.dst_arena, p.meta_offset), sizeof(rec), hipMemcpyDeviceToHost));
+        } else {
+            std::memcpy(&rec, &plan->h_meta[plan->dyn_index[idx]], sizeof(rec));
+            rec.data_flag = __atomic_load_n(&plan->h_flags[2 * idx], __ATOMIC_ACQUIRE);
+            rec.meta_flag = __atomic_load_n(&plan->h_flags[2 * idx + 1], __ATOMIC_ACQUIRE);
+        }
+        if (want_meta) {
+            plan->polled[plan->dyn_index[idx]] = rec;
+            plan->polled_valid[plan->dyn_index[idx]] = 1;
+        }
+        if (meta_out) *meta_out = rec;
+    } else if (meta_out) {
+        std::memset(meta_out, 0, sizeof(*meta_out));
+        const rdev_tensor_desc &d = plan->descs[idx];
+        meta_out->ndims = d.ndims;
+        meta_out->dtype = d.dtype;
+        meta_out->bytes = p.bytes;
+        for (uint32_t j = 0; j < d.ndims; ++j) meta_out->dims[j] = d.dims[j];
+        meta_out->tensor_id = p.tensor_id;
+        meta_out->seq = v;
+        meta_out->data_flag = v;
+        meta_out->dst_offset = plan->rpc_valid[idx] ? plan->rpc_offset[idx] : p.data_offset;
+    }
+    if (consume) {
+        __atomic_store_n(&plan->h_flags[widx], 0u, __ATOMIC_RELEASE);
+        std::vector<std::pair<uint32_t *, uint32_t>> f{{arena_flag, widx}};
+        RDEV_TRY(launch_inline_flags(plan, f, 0u, false, s));
+    }
+    return RDEV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,246 @@
+"""ctypes binding of librdev.so - argument marshalling only.
+
+Function names equal the C ABI's (include/rdev.h).  Every step of the transfer
+path runs inside the library; there is no Python or CPU fallback: if the shared
+library has not been built, importing a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librdev.so")
+
+MAX_DIMS = 8
+META_BYTES = 128
+DEFAULT_ALIGN = 256
+ALL_TENSORS = 0xFFFFFFFF
+HOST_ONLY = -1
+
+OK, NOT_READY = 0, 1
+E_INVAL, E_NOMEM, E_OVERLAP, E_ALIGN, E_RANGE, E_OVERFLOW, E_BUSY, E_HIP, E_STATE = range(-1, -10, -1)
+_ERR_NAMES = {E_INVAL: "E_INVAL", E_NOMEM: "E_NOMEM", E_OVERLAP: "E_OVERLAP", E_ALIGN: "E_ALIGN",
+              E_RANGE: "E_RANGE", E_OVERFLOW: "E_OVERFLOW", E_BUSY: "E_BUSY", E_HIP: "E_HIP", E_STATE: "E_STATE"}
+
+U8, I8, I16, I32, I64, F16, BF16, F32, F64 = range(9)
+DTYPE = {"u8": U8, "i8": I8, "i16": I16, "i32": I32, "i64": I64, "f16": F16, "bf16": BF16, "f32": F32, "f64": F64}
+STATIC, DYNAMIC = 0, 1
+ZEROCOPY, RPC2, RPC3, SENDERCOPY = 0, 1, 2, 3
+POLL_CONSUME, POLL_META, POLL_ARENA = 1, 2, 4
+PLAN_CHECK_BUSY = 1
+
+
+class Region(C.Structure):
+    _fields_ = [("arena_id", C.c_uint32), ("_pad", C.c_uint32), ("offset", C.c_uint64), ("bytes", C.c_uint64)]
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("tensor_id", C.c_uint32), ("dtype", C.c_uint32), ("ndims", C.c_uint32),
+                ("dst_arena", C.c_uint32), ("dims", C.c_int64 * MAX_DIMS)]
+
+
+class Placement(C.Structure):
+    _fields_ = [("tensor_id", C.c_uint32), ("kind", C.c_uint32), ("dst_arena", C.c_uint32), ("_pad", C.c_uint32),
+                ("data_offset", C.c_uint64), ("bytes", C.c_uint64), ("flag_offset", C.c_uint64),
+                ("meta_offset", C.c_uint64), ("region_bytes", C.c_uint64)]
+
+
+class PlanOpts(C.Structure):
+    _fields_ = [("align", C.c_uint64), ("max_static_bytes", C.c_uint64), ("dyn_heap_bytes", C.c_uint64),
+                ("chunk_bytes", C.c_uint64), ("small_bytes", C.c_uint32), ("flags", C.c_uint32)]
+
+
+class Meta(C.Structure):
+    _fields_ = [("ndims", C.c_uint32), ("dtype", C.c_uint32), ("bytes", C.c_uint64), ("src_offset", C.c_uint64),
+                ("dims", C.c_int64 * MAX_DIMS), ("dst_offset", C.c_uint64), ("src_arena", C.c_uint32),
+                ("tensor_id", C.c_uint32), ("seq", C.c_uint32), ("reserved", C.c_uint32 * 3),
+                ("data_flag", C.c_uint32), ("meta_flag", C.c_uint32)]
+
+
+class Xfer(C.Structure):
+    _fields_ = [("tensor_id", C.c_uint32), ("ndims", C.c_uint32), ("src", C.c_void_p), ("dtype", C.c_uint32),
+                ("_pad", C.c_uint32), ("dims", C.c_int64 * MAX_DIMS)]
+
+
+class RdevError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{_ERR_NAMES.get(status, status)}: {msg}")
+        self.status = status
+
+
+_lib = None
+
+# every symbol include/rdev.h declares: name -> (restype, argtypes)
+_P = C.c_void_p
+SYMBOLS = {
+    "rdev_open": (C.c_int32, [C.POINTER(_P), C.c_int]),
+    "rdev_close": (C.c_int32, [_P]),
+    "rdev_last_error": (C.c_char_p, []),
+    "rdev_abi_sizes": (None, [C.POINTER(C.c_uint32)]),
+    "rdev_register_arena": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, C.POINTER(C.c_uint32)]),
+    "rdev_alloc_region": (C.c_int32, [_P, C.c_uint32, C.c_uint64, C.c_uint64, C.POINTER(Region)]),
+    "rdev_free_region": (C.c_int32, [_P, C.POINTER(Region)]),
+    "rdev_plan": (C.c_int32, [_P, C.POINTER(TensorDesc), C.c_uint32, C.POINTER(PlanOpts), C.POINTER(_P)]),
+    "rdev_plan_count": (C.c_int32, [_P, C.POINTER(C.c_uint32)]),
+    "rdev_plan_get": (C.c_int32, [_P, C.c_uint32, C.POINTER(Placement)]),
+    "rdev_plan_arena_info": (C.c_int32, [_P, C.c_uint32] + [C.POINTER(C.c_uint64)] * 4),
+    "rdev_plan_bind_sources": (C.c_int32, [_P, C.POINTER(_P), C.c_uint32]),
+    "rdev_plan_bind_buffers": (C.c_int32, [_P, C.POINTER(Region), C.POINTER(Region)]),
+    "rdev_dyn_reset": (C.c_int32, [_P]),
+    "rdev_plan_free": (C.c_int32, [_P]),
+    "rdev_write_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, C.c_uint32, _P]),
+    "rdev_read_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
+    "rdev_poll": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, C.POINTER(Meta), _P]),
+}
+
+
+def lib() -> C.CDLL:
+    """Load librdev.so (once).  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RdevError(E_HIP, f"{LIB_PATH} is missing: run `python -m paper_1805_08430_amd.build` "
+                                   "(there is no fallback path)")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(l, name)
+            fn.restype = res
+            fn.argtypes = args
+        sizes = (C.c_uint32 * 6)()
+        l.rdev_abi_sizes(sizes)
+        want = [C.sizeof(TensorDesc), C.sizeof(Placement), C.sizeof(PlanOpts), C.sizeof(Meta), C.sizeof(Xfer),
+                C.sizeof(Region)]
+        if list(sizes) != want:
+            raise RdevError(E_INVAL, f"ABI struct sizes differ: library {list(sizes)}, binding {want}")
+        _lib = l
+    return _lib
+
+
+def _check(st: int) -> int:
+    if st < 0:
+        raise RdevError(st, (lib().rdev_last_error() or b"").decode())
+    return st
+
+
+def rdev_last_error() -> str:
+    return (lib().rdev_last_error() or b"").decode()
+
+
+def rdev_open(hip_device: int = 0) -> int:
+    h = _P()
+    _check(lib().rdev_open(C.byref(h), hip_device))
+    return h.value
+
+
+def rdev_close(dev: int) -> None:
+    _check(lib().rdev_close(dev))
+
+
+def rdev_register_arena(dev: int, base: int, nbytes: int, arena_flags: int = 0) -> int:
+    out = C.c_uint32()
+    _check(lib().rdev_register_arena(dev, base, nbytes, arena_flags, C.byref(out)))
+    return out.value
+
+
+def rdev_alloc_region(dev: int, arena_id: int, nbytes: int, align: int = DEFAULT_ALIGN) -> Region:
+    r = Region()
+    _check(lib().rdev_alloc_region(dev, arena_id, nbytes, align, C.byref(r)))
+    return r
+
+
+def rdev_free_region(dev: int, region: Region) -> None:
+    _check(lib().rdev_free_region(dev, C.byref(region)))
+
+
+def make_desc(tensor_id: int, dtype: int, dims: Sequence[int], dst_arena: int) -> TensorDesc:
+    d = TensorDesc()
+    d.tensor_id, d.dtype, d.ndims, d.dst_arena = tensor_id, dtype, len(dims), dst_arena
+    for i, v in enumerate(dims[:MAX_DIMS]):
+        d.dims[i] = v
+    return d
+
+
+def rdev_plan(dev: int, descs: Sequence[TensorDesc], align: int = 0, max_static_bytes: int = 0,
+              dyn_heap_bytes: int = 0, chunk_bytes: int = 0, small_bytes: int = 0, flags: int = 0) -> int:
+    arr = (TensorDesc * max(len(descs), 1))(*descs)
+    o = PlanOpts(align, max_static_bytes, dyn_heap_bytes, chunk_bytes, small_bytes, flags)
+    h = _P()
+    _check(lib().rdev_plan(dev, arr, len(descs), C.byref(o), C.byref(h)))
+    return h.value
+
+
+def rdev_plan_count(plan: int) -> int:
+    n = C.c_uint32()
+    _check(lib().rdev_plan_count(plan, C.byref(n)))
+    return n.value
+
+
+def rdev_plan_get(plan: int, i: int) -> Placement:
+    p = Placement()
+    _check(lib().rdev_plan_get(plan, i, C.byref(p)))
+    return p
+
+
+def rdev_plan_arena_info(plan: int, arena_id: int) -> dict:
+    v = [C.c_uint64() for _ in range(4)]
+    _check(lib().rdev_plan_arena_info(plan, arena_id, *[C.byref(x) for x in v]))
+    return dict(base=v[0].value, static_bytes=v[1].value, heap_offset=v[2].value, heap_bytes=v[3].value)
+
+
+def rdev_plan_bind_sources(plan: int, src_ptrs: Sequence[Optional[int]]) -> None:
+    arr = (_P * max(len(src_ptrs), 1))(*[p if p else None for p in src_ptrs])
+    _check(lib().rdev_plan_bind_sources(plan, arr, len(src_ptrs)))
+
+
+def rdev_plan_bind_buffers(plan: int, send_buf: Region, recv_buf: Optional[Region] = None) -> None:
+    _check(lib().rdev_plan_bind_buffers(plan, C.byref(send_buf), C.byref(recv_buf) if recv_buf is not None else None))
+
+
+def rdev_dyn_reset(plan: int) -> None:
+    _check(lib().rdev_dyn_reset(plan))
+
+
+def rdev_plan_free(plan: int) -> None:
+    _check(lib().rdev_plan_free(plan))
+
+
+def make_xfer(tensor_id: int, src: Optional[int] = None, dtype: int = 0, dims: Sequence[int] = ()) -> Xfer:
+    x = Xfer()
+    x.tensor_id, x.ndims, x.src, x.dtype = tensor_id, len(dims), src, dtype
+    for i, v in enumerate(dims[:MAX_DIMS]):
+        x.dims[i] = v
+    return x
+
+
+def _xfers(x: Optional[Sequence[Xfer]]):
+    if not x:
+        return None, 0
+    return (Xfer * len(x))(*x), len(x)
+
+
+def rdev_write_batch(dev: int, plan: int, x: Optional[Sequence[Xfer]] = None, mode: int = ZEROCOPY, seq: int = 1,
+                     stream: int = 0) -> None:
+    arr, n = _xfers(x)
+    _check(lib().rdev_write_batch(dev, plan, arr, n, mode, seq, stream or None))
+
+
+def rdev_read_batch(dev: int, plan: int, x: Optional[Sequence[Xfer]] = None, seq: int = 1, stream: int = 0) -> None:
+    arr, n = _xfers(x)
+    _check(lib().rdev_read_batch(dev, plan, arr, n, seq, stream or None))
+
+
+def rdev_poll(dev: int, plan: int, tensor_id: int = ALL_TENSORS, poll_flags: int = 0, stream: int = 0,
+              want_meta: bool = False):
+    """Returns True/False (ready or not); with want_meta=True returns (ready, Meta-or-None)."""
+    m = Meta()
+    st = _check(lib().rdev_poll(dev, plan, tensor_id, poll_flags, C.byref(m) if want_meta else None, stream or None))
+    ready = st == OK
+    if want_meta:
+        return ready, (m if ready else None)
+    return ready
+
+
+def placements(plan: int) -> List[Placement]:
+    return [rdev_plan_get(plan, i) for i in range(rdev_plan_count(plan))]
