@@ -251,6 +251,20 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
 rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
                       uint32_t poll_flags, rdev_meta *meta_out, void *stream);
 
+/* ---- measurement -------------------------------------------------------- */
+
+/* Time the batched copy kernel of whole-plan transfers (x == NULL) with HIP
+ * events recorded on the transfer's own stream, directly before and after that
+ * kernel (the flag kernel that follows is outside the bracket).  Up to
+ * max_samples launches are kept; max_samples == 0 switches timing off.
+ * Section 5 reports means over runs of 100 iterations; this gives the per-launch
+ * figure those means are made of. */
+rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples);
+/* Waits for the recorded events, writes the durations in milliseconds of the
+ * launches timed since the last read (at most cap) to ms_out (host pointer),
+ * their number to *n_out, and starts over. */
+rdev_status rdev_plan_profile_read(rdev_plan_t *plan, float *ms_out, uint32_t cap, uint32_t *n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -154,21 +154,25 @@ __global__ __launch_bounds__(kBlockThreads) void copy_inline_kernel(InlineBatch 
 }
 
 // flag <- value for a table of tensors; the host-visible word (if any) after the in-arena word.
+// The payload these flags announce was written by the kernel enqueued before this
+// one on the same stream, so it is already visible when this kernel starts: the
+// stores here need the right scope (agent / system) but no fence of their own,
+// which would cost an L2 write-back per lane.
 __global__ void flag_table_kernel(const FlagEnt *__restrict__ ents, uint32_t n, uint32_t value,
                                   uint32_t *mirror) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (mirror)
-        __hip_atomic_store(mirror + ents[i].mirror_idx, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(mirror + ents[i].mirror_idx, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 __global__ void flag_inline_kernel(InlineFlags f, uint32_t *mirror) {
     const uint32_t i = threadIdx.x;
     if (i >= f.n) return;
-    __hip_atomic_store(f.arena_flag[i], f.value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(f.arena_flag[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (mirror)
-        __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Dynamic path, sender side: 120 bytes of metadata into the receiver's slot

@@ -110,6 +110,10 @@ struct rdev_plan_s {
     std::vector<uint64_t> rpc_offset;                // per index: fresh allocation of the last RPC-mode delivery
     std::vector<uint8_t> rpc_valid;
 
+    // optional timing of the batched copy kernel
+    std::vector<hipEvent_t> ev_start, ev_stop;
+    uint32_t ev_used = 0;
+
     // buffers of the copying modes
     bool have_send = false, have_recv = false;
     rdev_region send_buf{}, recv_buf{};
@@ -269,8 +273,17 @@ void free_plan_blocks(rdev_plan_t *plan) {
     plan->blocks.clear();
 }
 
+void drop_events(rdev_plan_t *plan) {
+    for (hipEvent_t e : plan->ev_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : plan->ev_stop) (void)hipEventDestroy(e);
+    plan->ev_start.clear();
+    plan->ev_stop.clear();
+    plan->ev_used = 0;
+}
+
 void destroy_plan(rdev_plan_t *plan) {
     free_plan_blocks(plan);
+    drop_events(plan);
     if (plan->h_flags) (void)hipHostFree(plan->h_flags);
     if (plan->h_meta) (void)hipHostFree(plan->h_meta);
     plan->dev->n_plans--;
@@ -564,9 +577,12 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
                 return fail(RDEV_E_BUSY, "tensor " + std::to_string(plan->pl[i].tensor_id) + " has not been consumed");
     }
     if (plan->n_blocks) {
+        const bool timed = plan->ev_used < plan->ev_start.size();
+        if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
         hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_blocks), dim3(rdev::kBlockThreads), 0, s,
                            plan->d_items.ptr, plan->d_subs.ptr);
         RDEV_TRY(launch_check("copy_table_kernel"));
+        if (timed) HIP_TRY(hipEventRecord(plan->ev_stop[plan->ev_used++], s));
     }
     if (plan->n_static) {
         hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
@@ -823,6 +839,35 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
         std::vector<std::pair<uint32_t *, uint32_t>> f{{arena_flag, widx}};
         RDEV_TRY(launch_inline_flags(plan, f, 0u, false, s));
     }
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples) {
+    if (!plan) return fail(RDEV_E_INVAL, "NULL argument");
+    RDEV_TRY(require_gpu(plan->dev));
+    HIP_TRY(hipSetDevice(plan->dev->hip_device));
+    HIP_TRY(hipDeviceSynchronize());
+    drop_events(plan);
+    for (uint32_t i = 0; i < max_samples; ++i) {
+        hipEvent_t a, b;
+        HIP_TRY(hipEventCreate(&a));
+        plan->ev_start.push_back(a);
+        HIP_TRY(hipEventCreate(&b));
+        plan->ev_stop.push_back(b);
+    }
+    return RDEV_OK;
+}
+
+rdev_status rdev_plan_profile_read(rdev_plan_t *plan, float *ms_out, uint32_t cap, uint32_t *n_out) {
+    if (!plan || !n_out || (!ms_out && cap)) return fail(RDEV_E_INVAL, "NULL argument");
+    RDEV_TRY(require_gpu(plan->dev));
+    uint32_t n = std::min(cap, plan->ev_used);
+    for (uint32_t i = 0; i < n; ++i) {
+        HIP_TRY(hipEventSynchronize(plan->ev_stop[i]));
+        HIP_TRY(hipEventElapsedTime(&ms_out[i], plan->ev_start[i], plan->ev_stop[i]));
+    }
+    *n_out = n;
+    plan->ev_used = 0;
     return RDEV_OK;
 }
 

@@ -93,6 +93,8 @@ SYMBOLS = {
     "rdev_write_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, C.c_uint32, _P]),
     "rdev_read_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
     "rdev_poll": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, C.POINTER(Meta), _P]),
+    "rdev_plan_profile": (C.c_int32, [_P, C.c_uint32]),
+    "rdev_plan_profile_read": (C.c_int32, [_P, C.POINTER(C.c_float), C.c_uint32, C.POINTER(C.c_uint32)]),
 }
 
 
@@ -240,6 +242,17 @@ def rdev_poll(dev: int, plan: int, tensor_id: int = ALL_TENSORS, poll_flags: int
     if want_meta:
         return ready, (m if ready else None)
     return ready
+
+
+def rdev_plan_profile(plan: int, max_samples: int) -> None:
+    _check(lib().rdev_plan_profile(plan, max_samples))
+
+
+def rdev_plan_profile_read(plan: int, cap: int) -> List[float]:
+    buf = (C.c_float * max(cap, 1))()
+    n = C.c_uint32()
+    _check(lib().rdev_plan_profile_read(plan, buf, cap, C.byref(n)))
+    return [buf[i] for i in range(n.value)]
 
 
 def placements(plan: int) -> List[Placement]:
