@@ -396,6 +396,7 @@ def static_write(dev: Device, pl: Plan, sources: Dict[int, Tuple[int, int]], seq
         data = dev.arenas[sa].mem[so:so + p.nbytes].copy()
         dev._store("payload", t, p.dst_arena, p.data_offset, data)
         dev._store_u32("flag_set", t, p.dst_arena, p.flag_offset, seq)
+        pl.rpc_offsets.pop(t, None)         # the tensor now sits in its static region again
 
 
 POLL_META, POLL_DATA = 0, 1

@@ -204,4 +204,69 @@ __global__ void post_pull_kernel(PostBatch b, uint32_t *mirror_flags, rdev_meta 
     __hip_atomic_store(mirror_flags + b.flag_idx[i], b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+// ---- the copying alternatives the paper argues against (sections 2.2, 5.1) ----
+
+constexpr uint32_t kMaxHeapSlots = 16;
+struct HeapBases {
+    uint8_t *base[kMaxHeapSlots];   // start of the fresh-allocation area of each destination arena for this call
+};
+
+// One unit of unpack work: a chunk of one message's payload.  Grouping as in Item.
+struct UItem {
+    const uint8_t *hdr;     // the message (header first) in the receive buffer
+    uint64_t dst_rel;       // offset of the tensor inside this call's fresh-allocation area
+    uint32_t chunk_index;
+    uint32_t heap_slot;
+    uint32_t n_sub;
+    uint32_t sub_first;
+};
+static_assert(sizeof(UItem) == 32, "UItem is 32 bytes");
+
+// pack, part 1: the 128-byte header of every message (seq patched in) and the zero padding behind the payload
+__global__ void rpc_header_kernel(const rdev_meta *__restrict__ headers, uint8_t *const *__restrict__ msg_ptrs,
+                                  uint32_t n, uint32_t seq) {
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t t = gid >> 5, w = gid & 31;
+    if (t >= n) return;
+    const uint32_t *hw = (const uint32_t *)(headers + t);
+    uint8_t *msg = msg_ptrs[t];
+    ((uint32_t *)msg)[w] = (w == 26) ? seq : hw[w];
+    const uint64_t bytes = headers[t].bytes;
+    const uint32_t pad = (16 - (uint32_t)(bytes & 15)) & 15;
+    if (w < pad) msg[RDEV_META_BYTES + bytes + w] = 0;
+}
+
+__device__ __forceinline__ void unpack_one(const UItem &it, const HeapBases &hb, uint32_t chunk, uint32_t tid,
+                                           uint32_t nth) {
+    const uint64_t bytes = ((const rdev_meta *)it.hdr)->bytes;    // length comes from the message itself
+    const uint64_t off = (uint64_t)it.chunk_index * chunk;
+    if (off >= bytes) return;
+    const uint64_t rem = bytes - off;
+    const uint32_t n = rem < chunk ? (uint32_t)rem : chunk;
+    copy_span(it.hdr + RDEV_META_BYTES + off, hb.base[it.heap_slot] + it.dst_rel + off, n, tid, nth);
+}
+
+// unpack: parse each header, copy the payload out into the fresh allocation
+__global__ __launch_bounds__(kBlockThreads) void unpack_table_kernel(const UItem *__restrict__ items,
+                                                                      const UItem *__restrict__ subs, HeapBases hb,
+                                                                      uint32_t chunk) {
+    const UItem it = items[blockIdx.x];
+    if (it.n_sub == 0) {
+        unpack_one(it, hb, chunk, threadIdx.x, kBlockThreads);
+    } else {
+        const uint32_t wave = threadIdx.x >> 6;
+        if (wave < it.n_sub) unpack_one(subs[it.sub_first + wave], hb, chunk, threadIdx.x & 63, 64);
+    }
+}
+
+// flags of delivered messages: the value is the seq found in each header
+__global__ void rpc_flag_kernel(const FlagEnt *__restrict__ ents, uint8_t *const *__restrict__ hdr_ptrs, uint32_t n,
+                                uint32_t *mirror) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t seq = ((const rdev_meta *)hdr_ptrs[i])->seq;
+    __hip_atomic_store(ents[i].arena_flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(mirror + ents[i].mirror_idx, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 }  // namespace rdev

@@ -114,9 +114,21 @@ struct rdev_plan_s {
     std::vector<hipEvent_t> ev_start, ev_stop;
     uint32_t ev_used = 0;
 
-    // buffers of the copying modes
+    // buffers and tables of the copying modes (built on first use)
     bool have_send = false, have_recv = false;
     rdev_region send_buf{}, recv_buf{};
+    bool copy_tables = false;
+    uint64_t msg_total = 0;                          // packed bytes of the whole plan
+    uint64_t stage_end = 0;                          // end of the last staged tensor
+    std::vector<uint32_t> heap_slot_arena;           // heap slot -> destination arena
+    std::vector<uint64_t> heap_need;                 // per slot: fresh-allocation bytes of one whole-plan delivery
+    std::vector<uint64_t> rpc_rel;                   // per index: offset inside the slot's area
+    std::vector<uint32_t> rpc_slot;                  // per index
+    DevBuf<Item> d_pack_items, d_pack_subs, d_stage_items, d_stage_subs, d_unstage_items, d_unstage_subs;
+    DevBuf<rdev::UItem> d_unpack_send_items, d_unpack_send_subs, d_unpack_recv_items, d_unpack_recv_subs;
+    DevBuf<rdev_meta> d_headers;
+    DevBuf<uint8_t *> d_msg_send, d_msg_recv;
+    uint32_t n_pack_blocks = 0, n_stage_blocks = 0, n_unpack_blocks = 0;
 };
 
 namespace {
@@ -534,8 +546,205 @@ rdev_status rdev_plan_bind_sources(rdev_plan_t *plan, const void *const *src_ptr
     plan->n_blocks = (uint32_t)items.size();
     plan->src = std::move(locs);
     plan->bound_all = all;
+    plan->copy_tables = false;
     return RDEV_OK;
 }
+
+namespace {
+
+// Tables of the copying modes for a whole-plan batch: message layout (header ||
+// payload || pad to 16, back to back), staging layout (align-spaced), and the
+// per-arena layout of the fresh allocations an unpack makes.
+rdev_status build_copy_tables(rdev_plan_t *plan) {
+    rdev_device_t *dev = plan->dev;
+    const uint32_t n = (uint32_t)plan->pl.size();
+    const uint64_t chunk = plan->opts.chunk_bytes, A = plan->opts.align;
+    const uint32_t small = plan->opts.small_bytes;
+    if (!plan->have_send) return fail(RDEV_E_STATE, "copying modes need rdev_plan_bind_buffers");
+    if (!plan->bound_all) return fail(RDEV_E_STATE, "not every static tensor has a bound source");
+    if (plan->arenas.size() > rdev::kMaxHeapSlots) return fail(RDEV_E_INVAL, "copying modes support at most 16 destination arenas");
+    std::map<uint32_t, uint32_t> slot_of;
+    plan->heap_slot_arena.clear();
+    for (auto &kv : plan->arenas) {
+        slot_of[kv.first] = (uint32_t)plan->heap_slot_arena.size();
+        plan->heap_slot_arena.push_back(kv.first);
+    }
+    plan->heap_need.assign(plan->heap_slot_arena.size(), 0);
+    plan->rpc_rel.assign(n, 0);
+    plan->rpc_slot.assign(n, 0);
+    uint8_t *sb = dev->arenas[plan->send_buf.arena_id].base + plan->send_buf.offset;
+    uint8_t *rb = plan->have_recv ? dev->arenas[plan->recv_buf.arena_id].base + plan->recv_buf.offset : nullptr;
+
+    std::vector<Item> pack, pack_s, stage, stage_s, unstage, unstage_s, pend_a, pend_b, pend_c;
+    std::vector<rdev::UItem> us, us_s, ur, ur_s, upend_s, upend_r;
+    std::vector<rdev_meta> headers;
+    std::vector<uint8_t *> msg_send, msg_recv;
+    uint64_t mptr = 0, sptr = 0;
+    plan->stage_end = 0;
+    auto push_unpack = [&](std::vector<rdev::UItem> &items, std::vector<rdev::UItem> &subs, std::vector<rdev::UItem> &pend,
+                           const uint8_t *hdr, uint64_t rel, uint32_t slot, uint64_t bytes) {
+        if (bytes <= small) {
+            pend.push_back(rdev::UItem{hdr, rel, 0, slot, 0, 0});
+            if (pend.size() == rdev::kWavesPerBlock) {
+                items.push_back(rdev::UItem{nullptr, 0, 0, 0, (uint32_t)pend.size(), (uint32_t)subs.size()});
+                subs.insert(subs.end(), pend.begin(), pend.end());
+                pend.clear();
+            }
+            return;
+        }
+        for (uint64_t off = 0, c = 0; off < bytes; off += chunk, ++c)
+            items.push_back(rdev::UItem{hdr, rel, (uint32_t)c, slot, 0, 0});
+    };
+    for (uint32_t i = 0; i < n; ++i) {
+        const rdev_placement &p = plan->pl[i];
+        if (p.kind != RDEV_STATIC) continue;
+        const rdev_tensor_desc &d = plan->descs[i];
+        const SrcLoc &loc = plan->src[i];
+        const uint8_t *src = dev->arenas[loc.arena].base + loc.offset;
+        // message
+        rdev_meta h{};
+        h.ndims = d.ndims;
+        h.dtype = d.dtype;
+        h.bytes = p.bytes;
+        h.src_offset = loc.offset;
+        for (uint32_t j = 0; j < d.ndims; ++j) h.dims[j] = d.dims[j];
+        h.src_arena = loc.arena;
+        h.tensor_id = p.tensor_id;
+        headers.push_back(h);
+        msg_send.push_back(sb + mptr);
+        msg_recv.push_back(rb ? rb + mptr : nullptr);
+        cut_items(src, sb + mptr + RDEV_META_BYTES, p.bytes, i, chunk, small, pack, pack_s, pend_a);
+        const uint32_t slot = slot_of[p.dst_arena];
+        plan->rpc_slot[i] = slot;
+        plan->rpc_rel[i] = plan->heap_need[slot];
+        push_unpack(us, us_s, upend_s, sb + mptr, plan->rpc_rel[i], slot, p.bytes);
+        if (rb) push_unpack(ur, ur_s, upend_r, rb + mptr, plan->rpc_rel[i], slot, p.bytes);
+        plan->heap_need[slot] += (p.bytes + A - 1) & ~(A - 1);
+        mptr += RDEV_META_BYTES + ((p.bytes + 15) & ~(uint64_t)15);
+        // staging
+        plan->stage_end = std::max(plan->stage_end, sptr + p.bytes);
+        cut_items(src, sb + sptr, p.bytes, i, chunk, small, stage, stage_s, pend_b);
+        cut_items(sb + sptr, arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, i, chunk, small, unstage, unstage_s, pend_c);
+        sptr += (p.bytes + A - 1) & ~(A - 1);
+    }
+    flush_small(pack, pack_s, pend_a);
+    flush_small(stage, stage_s, pend_b);
+    flush_small(unstage, unstage_s, pend_c);
+    if (!upend_s.empty()) {
+        us.push_back(rdev::UItem{nullptr, 0, 0, 0, (uint32_t)upend_s.size(), (uint32_t)us_s.size()});
+        us_s.insert(us_s.end(), upend_s.begin(), upend_s.end());
+    }
+    if (!upend_r.empty()) {
+        ur.push_back(rdev::UItem{nullptr, 0, 0, 0, (uint32_t)upend_r.size(), (uint32_t)ur_s.size()});
+        ur_s.insert(ur_s.end(), upend_r.begin(), upend_r.end());
+    }
+    plan->msg_total = mptr;
+    HIP_TRY(hipSetDevice(dev->hip_device));
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(plan->d_pack_items.upload(pack));
+    HIP_TRY(plan->d_pack_subs.upload(pack_s));
+    HIP_TRY(plan->d_stage_items.upload(stage));
+    HIP_TRY(plan->d_stage_subs.upload(stage_s));
+    HIP_TRY(plan->d_unstage_items.upload(unstage));
+    HIP_TRY(plan->d_unstage_subs.upload(unstage_s));
+    HIP_TRY(plan->d_unpack_send_items.upload(us));
+    HIP_TRY(plan->d_unpack_send_subs.upload(us_s));
+    HIP_TRY(plan->d_unpack_recv_items.upload(ur));
+    HIP_TRY(plan->d_unpack_recv_subs.upload(ur_s));
+    HIP_TRY(plan->d_headers.upload(headers));
+    HIP_TRY(plan->d_msg_send.upload(msg_send));
+    HIP_TRY(plan->d_msg_recv.upload(msg_recv));
+    plan->n_pack_blocks = (uint32_t)pack.size();
+    plan->n_stage_blocks = (uint32_t)stage.size();
+    plan->n_unpack_blocks = (uint32_t)us.size();
+    plan->copy_tables = true;
+    return RDEV_OK;
+}
+
+rdev_status check_busy_all(rdev_plan_t *plan) {
+    if (!(plan->opts.flags & RDEV_PLAN_CHECK_BUSY)) return RDEV_OK;
+    for (uint32_t i = 0; i < plan->pl.size(); ++i)
+        if (plan->pl[i].kind == RDEV_STATIC && __atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE))
+            return fail(RDEV_E_BUSY, "tensor " + std::to_string(plan->pl[i].tensor_id) + " has not been consumed");
+    return RDEV_OK;
+}
+
+// whole-plan batch through one of the copying modes
+rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipStream_t s) {
+    if (!plan->copy_tables) RDEV_TRY(build_copy_tables(plan));
+    RDEV_TRY(check_busy_all(plan));
+    const uint32_t grid_tbl = (plan->n_static + 255) / 256;
+    if (mode == RDEV_SENDERCOPY) {
+        if (plan->stage_end > plan->send_buf.bytes) return fail(RDEV_E_NOMEM, "staging buffer too small");
+        std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
+        if (plan->n_stage_blocks) {
+            hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_stage_blocks), dim3(rdev::kBlockThreads), 0, s,
+                               plan->d_stage_items.ptr, plan->d_stage_subs.ptr);
+            RDEV_TRY(launch_check("copy_table_kernel(stage)"));
+            hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_stage_blocks), dim3(rdev::kBlockThreads), 0, s,
+                               plan->d_unstage_items.ptr, plan->d_unstage_subs.ptr);
+            RDEV_TRY(launch_check("copy_table_kernel(write)"));
+        }
+        if (plan->n_static) {
+            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(grid_tbl), dim3(256), 0, s, plan->d_flags.ptr,
+                               plan->n_static, seq, plan->d_flags_view);
+            RDEV_TRY(launch_check("flag_table_kernel"));
+        }
+        return RDEV_OK;
+    }
+    const bool wire = mode == RDEV_RPC3;
+    if (plan->msg_total > plan->send_buf.bytes) return fail(RDEV_E_NOMEM, "message buffer too small");
+    if (wire && (!plan->have_recv || plan->msg_total > plan->recv_buf.bytes)) return fail(RDEV_E_NOMEM, "receive buffer missing or too small");
+    rdev::HeapBases hb{};
+    for (size_t k = 0; k < plan->heap_slot_arena.size(); ++k) {
+        const ArenaLayout &al = plan->arenas[plan->heap_slot_arena[k]];
+        if (plan->heap_need[k] > al.heap_bytes - al.heap_ptr)
+            return fail(RDEV_E_NOMEM, "dynamic heap of arena " + std::to_string(plan->heap_slot_arena[k]) + " exhausted");
+    }
+    for (size_t k = 0; k < plan->heap_slot_arena.size(); ++k) {
+        ArenaLayout &al = plan->arenas[plan->heap_slot_arena[k]];
+        hb.base[k] = arena_ptr(plan, plan->heap_slot_arena[k], al.heap_offset + al.heap_ptr);
+    }
+    if (plan->n_static) {
+        // pack: headers, then payloads
+        hipLaunchKernelGGL(rdev::rpc_header_kernel, dim3((plan->n_static * 32 + 255) / 256), dim3(256), 0, s,
+                           plan->d_headers.ptr, plan->d_msg_send.ptr, plan->n_static, seq);
+        RDEV_TRY(launch_check("rpc_header_kernel"));
+        if (plan->n_pack_blocks) {
+            hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_pack_blocks), dim3(rdev::kBlockThreads), 0, s,
+                               plan->d_pack_items.ptr, plan->d_pack_subs.ptr);
+            RDEV_TRY(launch_check("copy_table_kernel(pack)"));
+        }
+        if (wire) {
+            uint8_t *sb = plan->dev->arenas[plan->send_buf.arena_id].base + plan->send_buf.offset;
+            uint8_t *rb = plan->dev->arenas[plan->recv_buf.arena_id].base + plan->recv_buf.offset;
+            std::vector<ResolvedStatic> one{ResolvedStatic{0, sb, rb, plan->msg_total}};
+            RDEV_TRY(launch_inline_copies(plan, one, s));
+        }
+        if (plan->n_unpack_blocks) {
+            hipLaunchKernelGGL(rdev::unpack_table_kernel, dim3(plan->n_unpack_blocks), dim3(rdev::kBlockThreads), 0, s,
+                               wire ? plan->d_unpack_recv_items.ptr : plan->d_unpack_send_items.ptr,
+                               wire ? plan->d_unpack_recv_subs.ptr : plan->d_unpack_send_subs.ptr, hb,
+                               (uint32_t)plan->opts.chunk_bytes);
+            RDEV_TRY(launch_check("unpack_table_kernel"));
+        }
+        hipLaunchKernelGGL(rdev::rpc_flag_kernel, dim3(grid_tbl), dim3(256), 0, s, plan->d_flags.ptr,
+                           wire ? plan->d_msg_recv.ptr : plan->d_msg_send.ptr, plan->n_static, plan->d_flags_view);
+        RDEV_TRY(launch_check("rpc_flag_kernel"));
+    }
+    // where each tensor went (for rdev_poll), and the heap pointers
+    for (uint32_t i = 0; i < plan->pl.size(); ++i) {
+        if (plan->pl[i].kind != RDEV_STATIC) continue;
+        const ArenaLayout &al = plan->arenas[plan->pl[i].dst_arena];
+        plan->rpc_offset[i] = al.heap_offset + al.heap_ptr + plan->rpc_rel[i];
+        plan->rpc_valid[i] = 1;
+    }
+    for (size_t k = 0; k < plan->heap_slot_arena.size(); ++k)
+        plan->arenas[plan->heap_slot_arena[k]].heap_ptr += plan->heap_need[k];
+    return RDEV_OK;
+}
+
+}  // namespace
 
 rdev_status rdev_plan_bind_buffers(rdev_plan_t *plan, const rdev_region *send_buf, const rdev_region *recv_buf) {
     if (!plan || !send_buf) return fail(RDEV_E_INVAL, "NULL argument");
@@ -547,6 +756,7 @@ rdev_status rdev_plan_bind_buffers(rdev_plan_t *plan, const rdev_region *send_bu
         if (r->offset > a->bytes || r->bytes > a->bytes - r->offset) return fail(RDEV_E_RANGE, "buffer outside its arena");
     }
     plan->send_buf = *send_buf;
+    plan->copy_tables = false;
     plan->have_send = true;
     plan->have_recv = recv_buf != nullptr;
     if (recv_buf) plan->recv_buf = *recv_buf;
@@ -571,6 +781,7 @@ rdev_status rdev_plan_free(rdev_plan_t *plan) {
 
 static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t s) {
     if (!plan->bound_all) return fail(RDEV_E_STATE, "not every static tensor has a bound source");
+    std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
     if (plan->opts.flags & RDEV_PLAN_CHECK_BUSY) {
         for (uint32_t i = 0; i < plan->pl.size(); ++i)
             if (plan->pl[i].kind == RDEV_STATIC && __atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE))
@@ -616,7 +827,10 @@ rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_x
     if (mode > RDEV_SENDERCOPY) return fail(RDEV_E_INVAL, "unknown mode");
     RDEV_TRY(require_gpu(dev));
     hipStream_t s = (hipStream_t)stream;
-    if (mode != RDEV_ZEROCOPY) return fail(RDEV_E_INVAL, "copying modes are not built in this version");
+    if (mode != RDEV_ZEROCOPY) {
+        if (x) return fail(RDEV_E_INVAL, "copying modes take the whole plan (x == NULL)");
+        return write_copy_mode(plan, mode, seq, s);
+    }
     if (!x) return write_static_all(plan, seq, s);
 
     // validate the whole batch first

@@ -1,0 +1,105 @@
+"""GPU parity for the copying alternatives (pack/unpack, pack/wire/unpack,
+sender staging copy): every arena - message buffers, receive buffers, receiver
+arenas with their fresh allocations - equals the CPU checker's image."""
+import numpy as np
+import pytest
+
+from oracle import rdev_oracle as O
+from paper_1805_08430_amd import rdev as R
+from paper_1805_08430_amd import workloads as W
+from helpers import OracleRun
+from test_gpu_static import _compare_all
+
+pytestmark = pytest.mark.gpu
+
+MODES = [(R.RPC2, O.MODE_RPC2), (R.RPC3, O.MODE_RPC3), (R.SENDERCOPY, O.MODE_SENDERCOPY)]
+
+
+def _sizes(wl, align=256):
+    msg = sum(128 + O.round_up(t.nbytes, 16) for t in wl.static_tensors)
+    stage = sum(O.round_up(t.nbytes, align) for t in wl.static_tensors)
+    return max(msg, stage) + 512, 2 * stage + 1024
+
+
+def _run_modes(wl, iters=2, **opts):
+    from gpu_harness import GpuRun
+    bufsz, heap = _sizes(wl)
+    g = GpuRun(wl, heap=heap, extra_arenas=(bufsz, bufsz), **opts)
+    o = OracleRun(wl, heap=heap, extra_arenas=(bufsz, bufsz))
+    gs = R.rdev_alloc_region(g.dev, g.extra_ids[0], bufsz - 256, 256)
+    gr = R.rdev_alloc_region(g.dev, g.extra_ids[1], bufsz - 256, 256)
+    os_ = o.dev.alloc_region(o.extra_ids[0], bufsz - 256, 256)
+    or_ = o.dev.alloc_region(o.extra_ids[1], bufsz - 256, 256)
+    assert (gs.offset, gr.offset) == (os_[1], or_[1])
+    R.rdev_plan_bind_buffers(g.plan, gs, gr)
+    static_ids = [i for i, t in enumerate(wl.tensors) if t.is_static]
+    seq = 0
+    for it in range(iters):
+        for gm, om in MODES + [(R.ZEROCOPY, None)]:
+            seq += 1
+            if it or seq > 1:
+                imgs = W.fill_sources(wl, variant=seq)
+                g.set_sources(imgs)
+                for sid, img in zip(o.send_ids, imgs):
+                    o.image(sid)[:] = img
+            R.rdev_dyn_reset(g.plan)
+            O.dyn_reset(o.plan)
+            R.rdev_write_batch(g.dev, g.plan, None, gm, seq, g.s)
+            if om is None:
+                O.static_write(o.dev, o.plan, o.sources, seq)
+            else:
+                O.copy_write(o.dev, o.plan, o.sources, om, seq, os_, or_)
+            assert g.wait_all()
+            _compare_all(g, o, f"mode {gm} seq {seq}")
+            for t in static_ids[:50]:
+                ok, m = R.rdev_poll(g.dev, g.plan, t, 0, g.s, want_meta=True)
+                ok2, m2 = O.poll(o.dev, o.plan, t)
+                p = o.plan.get(t)
+                assert ok and ok2 and m.seq == seq and m.bytes == p.nbytes
+                assert m.dst_offset == (m2["dst_offset"] if m2 else p.data_offset)
+            assert R.rdev_poll(g.dev, g.plan, R.ALL_TENSORS, R.POLL_CONSUME, g.s)
+            for t in static_ids:
+                assert O.poll(o.dev, o.plan, t, consume=True)[0]
+    _compare_all(g, o, "end")
+    g.close()
+
+
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_copy_modes_mixed_sets(seed):
+    _run_modes(W.small_mixed(seed, n=40, max_bytes=90000, n_recv=3, gran=1))
+
+
+def test_copy_modes_tiny_cutting():
+    _run_modes(W.small_mixed(24, n=20, max_bytes=20000, n_recv=2, gran=4), iters=1, chunk_bytes=1024, small_bytes=128)
+
+
+def test_copy_modes_inception_two_workers():
+    _run_modes(W.inception(2), iters=1)
+
+
+def test_copy_mode_errors():
+    from gpu_harness import GpuRun
+    wl = W.small_mixed(5, n=6, max_bytes=4000, n_recv=1)
+    bufsz, heap = _sizes(wl)
+    g = GpuRun(wl, heap=256, extra_arenas=(bufsz, bufsz))
+    o = OracleRun(wl, heap=256, extra_arenas=(bufsz, bufsz))
+
+    def status(fn, *a, **k):
+        with pytest.raises(R.RdevError) as e:
+            fn(*a, **k)
+        return e.value.status
+
+    assert status(R.rdev_write_batch, g.dev, g.plan, None, R.RPC2, 1, g.s) == R.E_STATE         # no buffers
+    small = R.rdev_alloc_region(g.dev, g.extra_ids[0], 256, 256)
+    R.rdev_plan_bind_buffers(g.plan, small, None)
+    assert status(R.rdev_write_batch, g.dev, g.plan, None, R.RPC2, 1, g.s) == R.E_NOMEM         # message buffer
+    assert status(R.rdev_write_batch, g.dev, g.plan, None, R.SENDERCOPY, 1, g.s) == R.E_NOMEM   # staging buffer
+    R.rdev_free_region(g.dev, small)
+    big = R.rdev_alloc_region(g.dev, g.extra_ids[0], bufsz - 256, 256)
+    R.rdev_plan_bind_buffers(g.plan, big, None)
+    assert status(R.rdev_write_batch, g.dev, g.plan, None, R.RPC3, 1, g.s) == R.E_NOMEM         # no receive buffer
+    assert status(R.rdev_write_batch, g.dev, g.plan, None, R.RPC2, 1, g.s) == R.E_NOMEM         # heap of 256 B
+    assert status(R.rdev_write_batch, g.dev, g.plan, [R.make_xfer(0)], R.RPC2, 1, g.s) == R.E_INVAL
+    assert status(R.rdev_write_batch, g.dev, g.plan, None, 7, 1, g.s) == R.E_INVAL
+    _compare_all(g, o, "failed calls move nothing")
+    g.close()
