@@ -39,29 +39,56 @@ def parse():
     ap.add_argument("--chunk-bytes", type=int, default=0)
     ap.add_argument("--small-bytes", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-modes", action="store_true", help="skip the untimed comparison with the copying modes")
+    ap.add_argument("--mode-steps", type=int, default=60)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a few plain device-to-device copies of known size (for counter calibration)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--time-every", type=int, default=8,
+                    help="bracket every n-th copy-kernel launch of a set with HIP events")
     return ap.parse_args()
 
 
 class TransferSet:
     """One copy of the workload: a sender arena set, receiver arenas, a plan."""
 
-    def __init__(self, R, torch, W, dev, wl, src_images, opts):
+    def __init__(self, R, torch, W, dev, wl, src_images, opts, copy_modes=False):
+        self.R, self.dev = R, dev
         self.send = [torch.from_numpy(img).to("cuda:0") for img in src_images]
-        for t in self.send:
-            R.rdev_register_arena(dev, t.data_ptr(), t.numel())
+        self.arena_ids = [R.rdev_register_arena(dev, t.data_ptr(), t.numel()) for t in self.send]
         need = [0] * wl.n_receiver_arenas
         for t in wl.tensors:
             if t.is_static:
                 need[t.dst_arena] += t.nbytes + 512 + 64
             else:
                 need[t.dst_arena] += 512
-        self.recv = [torch.empty(n + 1024, dtype=torch.uint8, device="cuda:0") for n in need]
+        heap = 0
+        if copy_modes:                      # fresh allocations of an unpack: the largest arena load, align-padded
+            heap = max(sum((t.nbytes + 255) // 256 * 256 for t in wl.static_tensors if t.dst_arena == a)
+                       for a in range(wl.n_receiver_arenas)) + 4096
+        self.recv = [torch.empty(n + heap + 1024, dtype=torch.uint8, device="cuda:0") for n in need]
         recv_ids = [R.rdev_register_arena(dev, t.data_ptr(), t.numel()) for t in self.recv]
+        self.arena_ids += recv_ids
+        self.regions = []
         descs = [R.make_desc(i, R.DTYPE[t.dtype], t.dims, recv_ids[t.dst_arena]) for i, t in enumerate(wl.tensors)]
-        self.plan = R.rdev_plan(dev, descs, **opts)
+        self.plan = R.rdev_plan(dev, descs, dyn_heap_bytes=heap, **opts)
+        if copy_modes:
+            nbuf = sum(128 + (t.nbytes + 255) // 256 * 256 for t in wl.static_tensors) + 4096
+            self.bufs = [torch.empty(nbuf, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+            ids = [R.rdev_register_arena(dev, b.data_ptr(), b.numel()) for b in self.bufs]
+            self.arena_ids += ids
+            regs = [R.rdev_alloc_region(dev, i, nbuf - 256, 256) for i in ids]
+            self.regions = regs
+            R.rdev_plan_bind_buffers(self.plan, regs[0], regs[1])
         ptrs = [self.send[t.src_arena].data_ptr() + t.src_offset if t.is_static else None for t in wl.tensors]
         R.rdev_plan_bind_sources(self.plan, ptrs)
+
+    def close(self):
+        self.R.rdev_plan_free(self.plan)
+        for r in self.regions:
+            self.R.rdev_free_region(self.dev, r)
+        for a in self.arena_ids:
+            self.R.rdev_unregister_arena(self.dev, a)
 
 
 def cpu_baseline(wl_name: str, seconds: float):
@@ -140,13 +167,16 @@ def main():
 
     seq = 0
 
-    def run(steps):
+    def run(steps, group=None, mode=R.ZEROCOPY):
         nonlocal seq
+        group = group or sets
         prev = None
         for k in range(steps):
-            ts = sets[k % rotate]
+            ts = group[k % len(group)]
             seq += 1
-            R.rdev_write_batch(dev, ts.plan, None, R.ZEROCOPY, seq, s)
+            if mode != R.ZEROCOPY:
+                R.rdev_dyn_reset(ts.plan)
+            R.rdev_write_batch(dev, ts.plan, None, mode, seq, s)
             if prev is not None:
                 wait_consume(prev)
             prev = ts
@@ -156,7 +186,7 @@ def main():
     stream.synchronize()
     per_set = -(-a.steps // rotate)
     for ts in sets:
-        R.rdev_plan_profile(ts.plan, per_set)
+        R.rdev_plan_profile(ts.plan, per_set, a.time_every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(a.steps)
@@ -167,7 +197,7 @@ def main():
     kernel_ms = []
     for ts in sets:
         kernel_ms += R.rdev_plan_profile_read(ts.plan, per_set)
-        R.rdev_plan_profile(ts.plan, 0)
+        R.rdev_plan_profile(ts.plan, 0, 1)
     ms_per_step = (t1 - t0) / a.steps * 1e3
     k_avg = sum(kernel_ms) / len(kernel_ms)
     algo_bytes = 2 * payload                                  # one read + one write per payload byte
@@ -198,13 +228,45 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None, "kernel_us_avg": round(k_avg * 1e3, 2),
                      "kernel_us_min": round(min(kernel_ms) * 1e3, 2), "kernel_us_max": round(max(kernel_ms) * 1e3, 2),
-                     "launches_timed": len(kernel_ms), "algorithmic_bytes_per_launch": algo_bytes},
+                     "launches_timed": len(kernel_ms), "timed_every": a.time_every, "algorithmic_bytes_per_launch": algo_bytes},
         "paper_context": {"note": "speed-ups the paper reports for its RDMA zero-copy transfer on 2 servers with "
                                   "100 Gbps InfiniBand (Xeon E5-2690v4, Tesla P100): context only",
                           "vs_grpc_tcp": "1.7x-61x", "vs_grpc_rdma": "1.3x-14x", "vs_rdma_sender_copy": "1.2x-1.8x"},
     }
     for ts in sets:
-        R.rdev_plan_free(ts.plan)
+        ts.close()
+    del sets
+    torch.cuda.empty_cache()
+
+    if not a.no_modes:
+        # untimed-for-`value` comparison: the same batch through the copying paths the paper replaces
+        images = W.fill_sources(wl, 0)
+        msets = [TransferSet(R, torch, W, dev, wl, images, opts, copy_modes=True) for _ in range(2)]
+        del images
+        res = {}
+        for name, mode in (("zerocopy", R.ZEROCOPY), ("sendercopy", R.SENDERCOPY), ("rpc2", R.RPC2), ("rpc3", R.RPC3)):
+            run(5, msets, mode)
+            torch.cuda.synchronize()
+            m0 = time.perf_counter()
+            run(a.mode_steps, msets, mode)
+            torch.cuda.synchronize()
+            res[name] = (time.perf_counter() - m0) / a.mode_steps * 1e6
+        out["modes"] = {"us_per_iteration": {k: round(v, 2) for k, v in res.items()},
+                        "slowdown_vs_zerocopy": {k: round(v / res["zerocopy"], 3) for k, v in res.items()},
+                        "algorithmic_hbm_bytes_per_payload_byte": {"zerocopy": 2, "sendercopy": 4, "rpc2": 4, "rpc3": 6},
+                        "steps_each": a.mode_steps, "rotating_sets": 2}
+        for ts in msets:
+            ts.close()
+        del msets
+    if a.calibrate:
+        nb = 256 << 20
+        x = torch.ones(nb, dtype=torch.uint8, device="cuda:0")
+        y = torch.empty_like(x)
+        with torch.cuda.stream(stream):
+            for _ in range(5):
+                y.copy_(x)
+        stream.synchronize()
+        out["calibration"] = {"plain_copy_bytes": nb, "copies": 5}
     R.rdev_close(dev)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a.workload, a.cpu_seconds)

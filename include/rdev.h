@@ -168,6 +168,11 @@ void rdev_abi_sizes(uint32_t out[6]);
 rdev_status rdev_register_arena(rdev_device_t *dev, void *base, uint64_t bytes,
                                 uint32_t arena_flags, uint32_t *arena_id_out);
 
+/* Forget an arena.  RDEV_E_BUSY while regions or plan blocks are still allocated
+ * in it; plans whose sources point into it must have been freed by the caller.
+ * Its id is not reused. */
+rdev_status rdev_unregister_arena(rdev_device_t *dev, uint32_t arena_id);
+
 /* Allocate / free a region inside an arena (section 3.1).  First fit from the
  * lowest address; align must be a power of two; bytes > 0.  rdev_free_region
  * takes exactly a region returned by rdev_alloc_region. */
@@ -255,11 +260,12 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
 
 /* Time the batched copy kernel of whole-plan transfers (x == NULL) with HIP
  * events recorded on the transfer's own stream, directly before and after that
- * kernel (the flag kernel that follows is outside the bracket).  Up to
- * max_samples launches are kept; max_samples == 0 switches timing off.
+ * kernel (the flag kernel that follows is outside the bracket).  Every
+ * `every`-th launch is timed (an event pair costs a few microseconds of stream
+ * time), up to max_samples of them; max_samples == 0 switches timing off.
  * Section 5 reports means over runs of 100 iterations; this gives the per-launch
  * figure those means are made of. */
-rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples);
+rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples, uint32_t every);
 /* Waits for the recorded events, writes the durations in milliseconds of the
  * launches timed since the last read (at most cap) to ms_out (host pointer),
  * their number to *n_out, and starts over. */

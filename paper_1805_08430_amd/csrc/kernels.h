@@ -14,6 +14,7 @@ namespace rdev {
 
 constexpr uint32_t kBlockThreads = 1024;     // 16 wavefronts
 constexpr uint32_t kWavesPerBlock = kBlockThreads / 64;
+constexpr uint32_t kXcds = 8;                // workgroup b is dispatched to XCD b % 8
 constexpr uint32_t kInlineMax = 8;           // explicit transfers per inline launch
 constexpr uint32_t kMetaInlineMax = 4;       // metadata records per launch (kernel-argument space)
 
@@ -238,6 +239,7 @@ __global__ void rpc_header_kernel(const rdev_meta *__restrict__ headers, uint8_t
 
 __device__ __forceinline__ void unpack_one(const UItem &it, const HeapBases &hb, uint32_t chunk, uint32_t tid,
                                            uint32_t nth) {
+    if (!it.hdr) return;                                          // padding entry of the table
     const uint64_t bytes = ((const rdev_meta *)it.hdr)->bytes;    // length comes from the message itself
     const uint64_t off = (uint64_t)it.chunk_index * chunk;
     if (off >= bytes) return;

@@ -112,7 +112,7 @@ struct rdev_plan_s {
 
     // optional timing of the batched copy kernel
     std::vector<hipEvent_t> ev_start, ev_stop;
-    uint32_t ev_used = 0;
+    uint32_t ev_used = 0, ev_every = 1, ev_count = 0;
 
     // buffers and tables of the copying modes (built on first use)
     bool have_send = false, have_recv = false;
@@ -134,7 +134,7 @@ struct rdev_plan_s {
 namespace {
 
 rdev_status arena_of(rdev_device_t *dev, uint32_t id, Arena **out) {
-    if (id >= dev->arenas.size()) return fail(RDEV_E_INVAL, "unknown arena " + std::to_string(id));
+    if (id >= dev->arenas.size() || !dev->arenas[id].bytes) return fail(RDEV_E_INVAL, "unknown arena " + std::to_string(id));
     *out = &dev->arenas[id];
     return RDEV_OK;
 }
@@ -197,6 +197,23 @@ void flush_small(std::vector<Item> &items, std::vector<Item> &subs, std::vector<
     items.push_back(Item{nullptr, nullptr, 0, (uint32_t)pending_small.size(), (uint32_t)subs.size(), 0});
     subs.insert(subs.end(), pending_small.begin(), pending_small.end());
     pending_small.clear();
+}
+
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD
+// b % 8), each XCD with its own L2.  Reorder the table so that every XCD walks
+// one contiguous eighth of the work instead of every eighth item: measured a
+// few percent faster for a streaming copy.  Padding entries do nothing.
+template <typename T>
+void xcd_order(std::vector<T> &items) {
+    const size_t n = items.size();
+    if (n < 2 * rdev::kXcds) return;
+    const size_t per = (n + rdev::kXcds - 1) / rdev::kXcds;
+    std::vector<T> out(per * rdev::kXcds, T{});
+    for (size_t b = 0; b < out.size(); ++b) {
+        const size_t c = (b % rdev::kXcds) * per + b / rdev::kXcds;
+        if (c < n) out[b] = items[c];
+    }
+    items.swap(out);
 }
 
 rdev_status require_gpu(const rdev_device_t *dev) {
@@ -362,6 +379,15 @@ rdev_status rdev_register_arena(rdev_device_t *dev, void *base, uint64_t bytes, 
     return RDEV_OK;
 }
 
+rdev_status rdev_unregister_arena(rdev_device_t *dev, uint32_t arena_id) {
+    if (!dev) return fail(RDEV_E_INVAL, "NULL argument");
+    Arena *a;
+    RDEV_TRY(arena_of(dev, arena_id, &a));
+    if (a->alloc.live()) return fail(RDEV_E_BUSY, "regions are still allocated in arena " + std::to_string(arena_id));
+    *a = Arena();
+    return RDEV_OK;
+}
+
 rdev_status rdev_alloc_region(rdev_device_t *dev, uint32_t arena_id, uint64_t bytes, uint64_t align, rdev_region *out) {
     if (!dev || !out) return fail(RDEV_E_INVAL, "NULL argument");
     Arena *a;
@@ -406,7 +432,8 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
     rdev_status st = rdev::layout(t, n, o.align, o.max_static_bytes, o.dyn_heap_bytes, plan->pl, plan->arenas, err);
     if (st != RDEV_OK) return fail(st, err);
     for (auto &kv : plan->arenas)
-        if (kv.first >= dev->arenas.size()) return fail(RDEV_E_INVAL, "unknown arena " + std::to_string(kv.first));
+        if (kv.first >= dev->arenas.size() || !dev->arenas[kv.first].bytes)
+            return fail(RDEV_E_INVAL, "unknown arena " + std::to_string(kv.first));
 
     // one block per destination arena from its sub-allocator (ascending arena id)
     for (auto &kv : plan->arenas) {
@@ -536,6 +563,7 @@ rdev_status rdev_plan_bind_sources(rdev_plan_t *plan, const void *const *src_ptr
                   plan->opts.small_bytes, items, subs, pending);
     }
     flush_small(items, subs, pending);
+    xcd_order(items);
     if (items.size() > 0x7fffffffull) return fail(RDEV_E_INVAL, "too many work items for one launch; raise chunk_bytes");
     if (plan->dev->gpu()) {
         HIP_TRY(hipSetDevice(plan->dev->hip_device));
@@ -639,6 +667,11 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
         ur_s.insert(ur_s.end(), upend_r.begin(), upend_r.end());
     }
     plan->msg_total = mptr;
+    xcd_order(pack);
+    xcd_order(stage);
+    xcd_order(unstage);
+    xcd_order(us);
+    xcd_order(ur);
     HIP_TRY(hipSetDevice(dev->hip_device));
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(plan->d_pack_items.upload(pack));
@@ -788,7 +821,7 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
                 return fail(RDEV_E_BUSY, "tensor " + std::to_string(plan->pl[i].tensor_id) + " has not been consumed");
     }
     if (plan->n_blocks) {
-        const bool timed = plan->ev_used < plan->ev_start.size();
+        const bool timed = plan->ev_used < plan->ev_start.size() && (plan->ev_count++ % plan->ev_every) == 0;
         if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
         hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_blocks), dim3(rdev::kBlockThreads), 0, s,
                            plan->d_items.ptr, plan->d_subs.ptr);
@@ -1056,8 +1089,10 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
     return RDEV_OK;
 }
 
-rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples) {
+rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples, uint32_t every) {
     if (!plan) return fail(RDEV_E_INVAL, "NULL argument");
+    plan->ev_every = every ? every : 1;
+    plan->ev_count = 0;
     RDEV_TRY(require_gpu(plan->dev));
     HIP_TRY(hipSetDevice(plan->dev->hip_device));
     HIP_TRY(hipDeviceSynchronize());

@@ -80,6 +80,7 @@ SYMBOLS = {
     "rdev_last_error": (C.c_char_p, []),
     "rdev_abi_sizes": (None, [C.POINTER(C.c_uint32)]),
     "rdev_register_arena": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, C.POINTER(C.c_uint32)]),
+    "rdev_unregister_arena": (C.c_int32, [_P, C.c_uint32]),
     "rdev_alloc_region": (C.c_int32, [_P, C.c_uint32, C.c_uint64, C.c_uint64, C.POINTER(Region)]),
     "rdev_free_region": (C.c_int32, [_P, C.POINTER(Region)]),
     "rdev_plan": (C.c_int32, [_P, C.POINTER(TensorDesc), C.c_uint32, C.POINTER(PlanOpts), C.POINTER(_P)]),
@@ -93,7 +94,7 @@ SYMBOLS = {
     "rdev_write_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, C.c_uint32, _P]),
     "rdev_read_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
     "rdev_poll": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, C.POINTER(Meta), _P]),
-    "rdev_plan_profile": (C.c_int32, [_P, C.c_uint32]),
+    "rdev_plan_profile": (C.c_int32, [_P, C.c_uint32, C.c_uint32]),
     "rdev_plan_profile_read": (C.c_int32, [_P, C.POINTER(C.c_float), C.c_uint32, C.POINTER(C.c_uint32)]),
 }
 
@@ -144,6 +145,10 @@ def rdev_register_arena(dev: int, base: int, nbytes: int, arena_flags: int = 0) 
     out = C.c_uint32()
     _check(lib().rdev_register_arena(dev, base, nbytes, arena_flags, C.byref(out)))
     return out.value
+
+
+def rdev_unregister_arena(dev: int, arena_id: int) -> None:
+    _check(lib().rdev_unregister_arena(dev, arena_id))
 
 
 def rdev_alloc_region(dev: int, arena_id: int, nbytes: int, align: int = DEFAULT_ALIGN) -> Region:
@@ -244,8 +249,8 @@ def rdev_poll(dev: int, plan: int, tensor_id: int = ALL_TENSORS, poll_flags: int
     return ready
 
 
-def rdev_plan_profile(plan: int, max_samples: int) -> None:
-    _check(lib().rdev_plan_profile(plan, max_samples))
+def rdev_plan_profile(plan: int, max_samples: int, every: int = 1) -> None:
+    _check(lib().rdev_plan_profile(plan, max_samples, every))
 
 
 def rdev_plan_profile_read(plan: int, cap: int) -> List[float]:

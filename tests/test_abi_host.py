@@ -181,7 +181,12 @@ def test_error_paths():
     assert _status(R.rdev_plan_bind_sources, plan, [_fake_base(0) + pl[0].data_offset + 2, None, None]) == R.E_OVERLAP
     assert _status(R.rdev_plan_bind_sources, plan, [None]) == R.E_INVAL
     R.rdev_plan_bind_sources(plan, [_fake_base(1), _fake_base(1) + 8, _fake_base(1) + 4096])
+    assert _status(R.rdev_unregister_arena, dev, ids[0]) == R.E_BUSY     # the plan's block lives there
     R.rdev_plan_free(plan)
+    R.rdev_unregister_arena(dev, ids[0])
+    assert _status(R.rdev_alloc_region, dev, ids[0], 16, 16) == R.E_INVAL
+    assert _status(R.rdev_unregister_arena, dev, ids[0]) == R.E_INVAL
+    assert R.rdev_register_arena(dev, _fake_base(0), 4096) == 2          # same memory again, new id
     R.rdev_close(dev)
 
 
