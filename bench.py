@@ -27,6 +27,29 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per copy-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what each
+# counter reads for a plain 256 MiB device-to-device copy (profiles/copy_table_kernel_<workload>.md).
+# Valid only for the kernel sources they were taken with: `hash` covers csrc/kernels.h + csrc/rdev.hip.
+TRAFFIC = {
+    "vgg16": {"hash": "e221b6cb015abb59", "fetch_bytes": 557730222, "write_bytes": 553469356},
+}
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("kernels.h", "rdev.hip"):
+        with open(os.path.join(ROOT, "paper_1805_08430_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    t = TRAFFIC.get(workload)
+    if not t or t["hash"] != kernel_source_hash():
+        return None                      # no counters for this workload, or the kernel changed since
+    return t["fetch_bytes"] + t["write_bytes"]
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -226,7 +249,7 @@ def main():
         "hbm_frac_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "kernel": "copy_table_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None, "kernel_us_avg": round(k_avg * 1e3, 2),
+                     "traffic": measured_traffic(a.workload), "kernel_us_avg": round(k_avg * 1e3, 2),
                      "kernel_us_min": round(min(kernel_ms) * 1e3, 2), "kernel_us_max": round(max(kernel_ms) * 1e3, 2),
                      "launches_timed": len(kernel_ms), "timed_every": a.time_every, "algorithmic_bytes_per_launch": algo_bytes},
         "paper_context": {"note": "speed-ups the paper reports for its RDMA zero-copy transfer on 2 servers with "
