@@ -86,6 +86,24 @@ class TransferSet:
             else:
                 need[t.dst_arena] += 512
         heap = 0
+        self.dyn_variants = []
+        dyn_ids = [i for i, t in enumerate(wl.tensors) if not t.is_static]
+        if dyn_ids and not copy_modes:
+            variants = dynamic_inputs(W, wl, 4)
+            nsrc = max(sum((len(p) + 511) // 256 * 256 for _, _, p in v) for v in variants) + 1024
+            self.dyn_src = torch.empty(4 * nsrc, dtype=torch.uint8, device="cuda:0")
+            self.arena_ids.append(R.rdev_register_arena(dev, self.dyn_src.data_ptr(), self.dyn_src.numel()))
+            heap = nsrc + 4096
+            for vi, v in enumerate(variants):
+                off = vi * nsrc
+                xs = []
+                for (dt, dims, payload), tid in zip(v, dyn_ids):
+                    self.dyn_src[off:off + len(payload)].copy_(torch.from_numpy(payload))
+                    xs.append(R.make_xfer(tid, self.dyn_src.data_ptr() + off, R.DTYPE[dt], dims))
+                    off += (len(payload) + 255) // 256 * 256
+                self.dyn_variants.append((xs, sum(len(p) for _, _, p in v)))
+            self.dyn_pull = [R.make_xfer(t) for t in dyn_ids]
+            self.dyn_ids = dyn_ids
         if copy_modes:                      # fresh allocations of an unpack: the largest arena load, align-padded
             heap = max(sum((t.nbytes + 255) // 256 * 256 for t in wl.static_tensors if t.dst_arena == a)
                        for a in range(wl.n_receiver_arenas)) + 4096
@@ -112,6 +130,24 @@ class TransferSet:
             self.R.rdev_free_region(self.dev, r)
         for a in self.arena_ids:
             self.R.rdev_unregister_arena(self.dev, a)
+
+
+def dynamic_inputs(W, wl, n_variants):
+    """Run-time shaped tensors of a few iterations: [(dtype, dims, payload bytes), ...] per iteration."""
+    import numpy as np
+    out = []
+    if wl.name == "tiny":
+        for it in range(n_variants):
+            rows = W.tiny_dynamic_rows(it)
+            out.append([("f32", (r, 256), W.dynamic_payload(r * 1024, 100 * it + k)) for k, r in enumerate(rows)])
+    elif wl.name == "lstm":
+        table = W.lstm_embedding_table()
+        for it in range(n_variants):
+            u = np.unique(W.lstm_token_ids(it).reshape(-1))
+            rows = np.ascontiguousarray(table[u])
+            out.append([("i64", (int(u.size),), u.astype(np.int64).view(np.uint8).copy()),
+                        ("f32", (int(u.size), W.LSTM_WIDTH), rows.view(np.uint8).reshape(-1).copy())])
+    return out
 
 
 def cpu_baseline(wl_name: str, seconds: float):
@@ -179,14 +215,24 @@ def main():
     del images
     stream = torch.cuda.Stream()
     s = stream.cuda_stream
+    stream2 = torch.cuda.Stream()           # dynamic-size traffic travels on its own queue
+    s2 = stream2.cuda_stream
+    has_dyn = bool(sets[0].dyn_variants)
+    dyn_bytes = (sum(b for _, b in sets[0].dyn_variants) / len(sets[0].dyn_variants)) if has_dyn else 0
     torch.cuda.synchronize()
 
-    def wait_consume(ts):
+    def spin(fn):
         spins = 0
-        while not R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, s):
+        while not fn():
             spins += 1
             if spins > 50_000_000:
-                raise RuntimeError("flags never became visible")
+                raise RuntimeError("flag never became visible")
+
+    def wait_consume(ts):
+        spin(lambda: R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, s))
+        if ts.dyn_variants:
+            for t in ts.dyn_ids:
+                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, s2))
 
     seq = 0
 
@@ -200,6 +246,14 @@ def main():
             if mode != R.ZEROCOPY:
                 R.rdev_dyn_reset(ts.plan)
             R.rdev_write_batch(dev, ts.plan, None, mode, seq, s)
+            if ts.dyn_variants:
+                # section 3.3: metadata + flag, receiver polls, allocates, pulls, raises payload-complete
+                R.rdev_dyn_reset(ts.plan)
+                xs, _ = ts.dyn_variants[k % len(ts.dyn_variants)]
+                R.rdev_write_batch(dev, ts.plan, xs, R.ZEROCOPY, seq, s2)
+                for t in ts.dyn_ids:
+                    spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_META | R.POLL_CONSUME, s2))
+                R.rdev_read_batch(dev, ts.plan, ts.dyn_pull, seq, s2)
             if prev is not None:
                 wait_consume(prev)
             prev = ts
@@ -214,6 +268,7 @@ def main():
     t0 = time.perf_counter()
     run(a.steps)
     stream.synchronize()
+    stream2.synchronize()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
@@ -228,7 +283,7 @@ def main():
     out = {
         "metric": "effective tensor-transfer GB/s (payload bytes delivered per second, zero-copy static path); "
                   "also us per iteration and fraction of HBM peak",
-        "value": round(payload / (ms_per_step * 1e-3) / 1e9, 2),
+        "value": round((payload + dyn_bytes) / (ms_per_step * 1e-3) / 1e9, 2),
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": a.steps,
@@ -243,7 +298,10 @@ def main():
                                f"{payload} payload bytes per iteration, {wl.n_sender_arenas} sender arena(s) -> "
                                f"{wl.n_receiver_arenas} receiver arena(s) in one HBM",
                    "rotating_sets": rotate, "chunk_bytes": a.chunk_bytes or 16384,
-                   "step": "write_batch (copy kernel + flag kernel) + poll/consume of the previous iteration"},
+                   "dynamic_payload_bytes_per_iteration": round(dyn_bytes),
+                   "step": "write_batch (copy kernel + flag kernel)" +
+                           (" + dynamic tensors: metadata write, metadata poll, allocate + pull, on a second stream"
+                            if has_dyn else "") + " + poll/consume of the previous iteration"},
         "us_per_iteration": round(ms_per_step * 1e3, 2),
         "hbm_gbs_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_frac_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -241,15 +241,17 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
                             uint32_t seq, void *stream);
 
 /* Non-blocking completion test (section 3.2: the receiver polls the flag,
- * clears it, then lets dependants run).  Reads the pinned host word that the
- * kernel stores with system-scope release after the in-arena flag, so no GPU
- * work is issued for a test (section 3.5: poll on the CPU side).
+ * clears it, then lets dependants run).  Reads pinned host words that the flag
+ * kernel stores with system scope - one word per listed tensor for explicit
+ * batches, one delivery token for a whole-plan batch - so no GPU work is issued
+ * for a test (section 3.5: poll on the CPU side).
  *   static tensor : ready when its flag != 0.
  *   dynamic tensor: RDEV_POLL_META tests the metadata flag (and remembers the
  *                   record for rdev_read_batch); otherwise the payload-complete flag.
  *   RDEV_ALL_TENSORS: ready when every static tensor of the plan is.
- * RDEV_POLL_CONSUME clears the flag on success: the host word at once, the
- * in-arena word by a small kernel enqueued on `stream`.
+ * RDEV_POLL_CONSUME clears the flag on success: the host side at once, the
+ * in-arena word by a small kernel enqueued on `stream`, which must be the stream
+ * the delivery was enqueued on (or one ordered after it).
  * RDEV_POLL_ARENA reads the in-arena word with a synchronous copy instead (slow; for checks).
  * meta_out (host pointer, may be NULL): dynamic tensors - the record as last
  * delivered; static tensors after an RPC-mode delivery - dst_offset of the fresh allocation. */

@@ -154,18 +154,18 @@ __global__ __launch_bounds__(kBlockThreads) void copy_inline_kernel(InlineBatch 
     copy_span(b.e[k].src + off, b.e[k].dst + off, n, threadIdx.x, kBlockThreads);
 }
 
-// flag <- value for a table of tensors; the host-visible word (if any) after the in-arena word.
+// flag <- value for a table of tensors (one lane each, in-arena words).
 // The payload these flags announce was written by the kernel enqueued before this
 // one on the same stream, so it is already visible when this kernel starts: the
-// stores here need the right scope (agent / system) but no fence of their own,
-// which would cost an L2 write-back per lane.
+// stores here need the right scope but no fence of their own, which would cost an
+// L2 write-back per lane.  The host is told with ONE word for the whole table
+// (a delivery token): per-tensor host words would be thousands of separate
+// writes across the host link for the many-small-tensor sets.
 __global__ void flag_table_kernel(const FlagEnt *__restrict__ ents, uint32_t n, uint32_t value,
-                                  uint32_t *mirror) {
+                                  uint32_t *batch_word, uint32_t token) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (mirror)
-        __hip_atomic_store(mirror + ents[i].mirror_idx, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (i < n) __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (batch_word && i == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 __global__ void flag_inline_kernel(InlineFlags f, uint32_t *mirror) {
@@ -263,12 +263,13 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_table_kernel(const UItem
 
 // flags of delivered messages: the value is the seq found in each header
 __global__ void rpc_flag_kernel(const FlagEnt *__restrict__ ents, uint8_t *const *__restrict__ hdr_ptrs, uint32_t n,
-                                uint32_t *mirror) {
+                                uint32_t *batch_word, uint32_t token) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const uint32_t seq = ((const rdev_meta *)hdr_ptrs[i])->seq;
-    __hip_atomic_store(ents[i].arena_flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(mirror + ents[i].mirror_idx, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (i < n) {
+        const uint32_t seq = ((const rdev_meta *)hdr_ptrs[i])->seq;
+        __hip_atomic_store(ents[i].arena_flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (i == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 }  // namespace rdev

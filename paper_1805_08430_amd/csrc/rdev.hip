@@ -104,6 +104,12 @@ struct rdev_plan_s {
 
     // host-visible words: flags[2*i] = completion / payload-complete, flags[2*i+1] = metadata flag
     uint32_t *h_flags = nullptr, *d_flags_view = nullptr;
+    // whole-plan deliveries are announced to the host by one word: h_flags[2*n] holds the token of the
+    // last one completed; a static tensor is ready when that token differs from the one it consumed
+    uint32_t *h_batch = nullptr, *d_batch_view = nullptr;
+    uint32_t issued_token = 0;
+    uint32_t seq_ring[16] = {0};
+    std::vector<uint32_t> consumed_token;
     rdev_meta *h_meta = nullptr, *d_meta_view = nullptr;
     std::vector<rdev_meta> polled;                   // record seen by the last metadata poll
     std::vector<uint8_t> polled_valid;
@@ -167,6 +173,25 @@ rdev_status index_of(const rdev_plan_t *plan, uint32_t tensor_id, uint32_t *idx)
 }
 
 uint8_t *arena_ptr(rdev_plan_t *plan, uint32_t arena, uint64_t off) { return plan->dev->arenas[arena].base + off; }
+
+// what a static tensor's completion shows to the host: its flag value, 0 = not ready
+uint32_t static_ready(const rdev_plan_t *plan, uint32_t i) {
+    const uint32_t v = __atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE);
+    if (v) return v;
+    const uint32_t tok = __atomic_load_n(plan->h_batch, __ATOMIC_ACQUIRE);
+    return tok != plan->consumed_token[i] ? plan->seq_ring[tok & 15] : 0;
+}
+
+void static_consume(rdev_plan_t *plan, uint32_t i) {
+    __atomic_store_n(&plan->h_flags[2 * i], 0u, __ATOMIC_RELEASE);
+    plan->consumed_token[i] = __atomic_load_n(plan->h_batch, __ATOMIC_ACQUIRE);
+}
+
+uint32_t next_token(rdev_plan_t *plan, uint32_t seq) {
+    if (++plan->issued_token == 0) ++plan->issued_token;      // 0 means "nothing delivered yet"
+    plan->seq_ring[plan->issued_token & 15] = seq;
+    return plan->issued_token;
+}
 
 rdev_status launch_check(const char *what) {
     hipError_t e = hipGetLastError();
@@ -474,12 +499,15 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
         };
         hipError_t e = hipSetDevice(dev->hip_device);
         if (e != hipSuccess) return bail(e, "hipSetDevice");
-        const size_t nflags = std::max<size_t>(2 * (size_t)n, 2);
+        const size_t nflags = 2 * (size_t)n + 2;
         e = hipHostMalloc((void **)&raw->h_flags, nflags * sizeof(uint32_t), hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { raw->h_flags = nullptr; return bail(e, "hipHostMalloc(flags)"); }
         std::memset(raw->h_flags, 0, nflags * sizeof(uint32_t));
         e = hipHostGetDevicePointer((void **)&raw->d_flags_view, raw->h_flags, 0);
         if (e != hipSuccess) return bail(e, "hipHostGetDevicePointer(flags)");
+        raw->h_batch = raw->h_flags + 2 * (size_t)n;
+        raw->d_batch_view = raw->d_flags_view + 2 * (size_t)n;
+        raw->consumed_token.assign(n, 0);
         const size_t nmeta = std::max<size_t>(raw->n_dyn, 1);
         e = hipHostMalloc((void **)&raw->h_meta, nmeta * sizeof(rdev_meta), hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { raw->h_meta = nullptr; return bail(e, "hipHostMalloc(meta)"); }
@@ -502,7 +530,7 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
         if (e != hipSuccess) return bail(e, "upload(flag table)");
         if (!fe.empty()) {
             hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(((uint32_t)fe.size() + 255) / 256), dim3(256), 0, 0,
-                               raw->d_flags.ptr, (uint32_t)fe.size(), 0u, (uint32_t *)nullptr);
+                               raw->d_flags.ptr, (uint32_t)fe.size(), 0u, (uint32_t *)nullptr, 0u);
             e = hipGetLastError();
             if (e != hipSuccess) return bail(e, "flag_table_kernel");
         }
@@ -697,7 +725,7 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
 rdev_status check_busy_all(rdev_plan_t *plan) {
     if (!(plan->opts.flags & RDEV_PLAN_CHECK_BUSY)) return RDEV_OK;
     for (uint32_t i = 0; i < plan->pl.size(); ++i)
-        if (plan->pl[i].kind == RDEV_STATIC && __atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE))
+        if (plan->pl[i].kind == RDEV_STATIC && static_ready(plan, i))
             return fail(RDEV_E_BUSY, "tensor " + std::to_string(plan->pl[i].tensor_id) + " has not been consumed");
     return RDEV_OK;
 }
@@ -720,7 +748,7 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
         }
         if (plan->n_static) {
             hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(grid_tbl), dim3(256), 0, s, plan->d_flags.ptr,
-                               plan->n_static, seq, plan->d_flags_view);
+                               plan->n_static, seq, plan->d_batch_view, next_token(plan, seq));
             RDEV_TRY(launch_check("flag_table_kernel"));
         }
         return RDEV_OK;
@@ -762,7 +790,8 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
             RDEV_TRY(launch_check("unpack_table_kernel"));
         }
         hipLaunchKernelGGL(rdev::rpc_flag_kernel, dim3(grid_tbl), dim3(256), 0, s, plan->d_flags.ptr,
-                           wire ? plan->d_msg_recv.ptr : plan->d_msg_send.ptr, plan->n_static, plan->d_flags_view);
+                           wire ? plan->d_msg_recv.ptr : plan->d_msg_send.ptr, plan->n_static, plan->d_batch_view,
+                           next_token(plan, seq));
         RDEV_TRY(launch_check("rpc_flag_kernel"));
     }
     // where each tensor went (for rdev_poll), and the heap pointers
@@ -815,11 +844,7 @@ rdev_status rdev_plan_free(rdev_plan_t *plan) {
 static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t s) {
     if (!plan->bound_all) return fail(RDEV_E_STATE, "not every static tensor has a bound source");
     std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
-    if (plan->opts.flags & RDEV_PLAN_CHECK_BUSY) {
-        for (uint32_t i = 0; i < plan->pl.size(); ++i)
-            if (plan->pl[i].kind == RDEV_STATIC && __atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE))
-                return fail(RDEV_E_BUSY, "tensor " + std::to_string(plan->pl[i].tensor_id) + " has not been consumed");
-    }
+    RDEV_TRY(check_busy_all(plan));
     if (plan->n_blocks) {
         const bool timed = plan->ev_used < plan->ev_start.size() && (plan->ev_count++ % plan->ev_every) == 0;
         if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
@@ -830,7 +855,7 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
     }
     if (plan->n_static) {
         hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
-                           plan->d_flags.ptr, plan->n_static, seq, plan->d_flags_view);
+                           plan->d_flags.ptr, plan->n_static, seq, plan->d_batch_view, next_token(plan, seq));
         RDEV_TRY(launch_check("flag_table_kernel"));
     }
     return RDEV_OK;
@@ -844,7 +869,7 @@ static rdev_status transfer_static_list(rdev_plan_t *plan, const std::vector<std
     for (size_t k = 0; k < list.size(); ++k) {
         RDEV_TRY(resolve_static(plan, list[k].first, list[k].second, &v[k]));
         const rdev_placement &p = plan->pl[list[k].first];
-        if ((plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && __atomic_load_n(&plan->h_flags[2 * list[k].first], __ATOMIC_ACQUIRE))
+        if ((plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && static_ready(plan, list[k].first))
             return fail(RDEV_E_BUSY, "tensor " + std::to_string(p.tensor_id) + " has not been consumed");
         flags.emplace_back((uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset), 2 * list[k].first);
     }
@@ -1027,12 +1052,12 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
     if (tensor_id == RDEV_ALL_TENSORS) {
         if (poll_flags & (RDEV_POLL_META | RDEV_POLL_ARENA)) return fail(RDEV_E_INVAL, "RDEV_ALL_TENSORS polls host-visible static flags only");
         for (uint32_t i = 0; i < plan->pl.size(); ++i)
-            if (plan->pl[i].kind == RDEV_STATIC && !__atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE)) return RDEV_NOT_READY;
+            if (plan->pl[i].kind == RDEV_STATIC && !static_ready(plan, i)) return RDEV_NOT_READY;
         if (consume && plan->n_static) {
             for (uint32_t i = 0; i < plan->pl.size(); ++i)
-                if (plan->pl[i].kind == RDEV_STATIC) __atomic_store_n(&plan->h_flags[2 * i], 0u, __ATOMIC_RELEASE);
+                if (plan->pl[i].kind == RDEV_STATIC) static_consume(plan, i);
             hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
-                               plan->d_flags.ptr, plan->n_static, 0u, (uint32_t *)nullptr);
+                               plan->d_flags.ptr, plan->n_static, 0u, (uint32_t *)nullptr, 0u);
             RDEV_TRY(launch_check("flag_table_kernel"));
         }
         return RDEV_OK;
@@ -1051,7 +1076,7 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
     if (poll_flags & RDEV_POLL_ARENA) {
         HIP_TRY(hipMemcpy(&v, arena_flag, sizeof(v), hipMemcpyDeviceToHost));
     } else {
-        v = __atomic_load_n(&plan->h_flags[widx], __ATOMIC_ACQUIRE);
+        v = dyn ? __atomic_load_n(&plan->h_flags[widx], __ATOMIC_ACQUIRE) : static_ready(plan, idx);
     }
     if (!v) return RDEV_NOT_READY;
 
@@ -1082,7 +1107,8 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
         meta_out->dst_offset = plan->rpc_valid[idx] ? plan->rpc_offset[idx] : p.data_offset;
     }
     if (consume) {
-        __atomic_store_n(&plan->h_flags[widx], 0u, __ATOMIC_RELEASE);
+        if (dyn) __atomic_store_n(&plan->h_flags[widx], 0u, __ATOMIC_RELEASE);
+        else static_consume(plan, idx);
         std::vector<std::pair<uint32_t *, uint32_t>> f{{arena_flag, widx}};
         RDEV_TRY(launch_inline_flags(plan, f, 0u, false, s));
     }
