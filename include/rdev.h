@@ -258,6 +258,56 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
 rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
                       uint32_t poll_flags, rdev_meta *meta_out, void *stream);
 
+/* ---- sender-side allocation-site tracing (section 3.4) ------------------- */
+
+/* A tensor can only be sent without a copy if its buffer was allocated in
+ * registered memory, and the buffer of a sent tensor may have been allocated
+ * several nodes upstream (in-place nodes pass buffers through).  The paper
+ * instruments the runtime's allocator: during the first mini-batch every
+ * allocation is recorded as address -> (node id, index of this allocation
+ * within the node's execution), a later allocation at the same address
+ * overwriting the earlier one; when a node sends a tensor its buffer address is
+ * looked up and the allocation site found is added to a set S; from the second
+ * mini-batch on, an allocation whose (node id, index) is in S is served from the
+ * allocator of the registered arena, every other one from the ordinary allocator.
+ *
+ * The tracer owns two sub-allocators: one over `pool` (caller-owned device
+ * memory that is NOT registered: the ordinary allocator) and the registered
+ * arena `arena_id`'s own (rdev_alloc_region).  Buffers are 256-byte aligned. */
+typedef struct rdev_tracer_s rdev_tracer_t;
+
+rdev_status rdev_tracer_open(rdev_device_t *dev, void *pool_base /* device pointer */, uint64_t pool_bytes,
+                             uint32_t arena_id, rdev_tracer_t **out);
+/* Releases every buffer and staging region still held, then the tracer. */
+rdev_status rdev_tracer_close(rdev_tracer_t *tr);
+/* Start of a mini-batch: every buffer and staging region of the previous one is
+ * released (the caller has waited for its transfers), per-node allocation
+ * indices restart at 0.  The first iteration begun is the tracing iteration. */
+rdev_status rdev_tracer_begin_iteration(rdev_tracer_t *tr);
+/* The instrumented allocator.  *alloc_index_out = how many allocations node_id
+ * made before this one in the current iteration; *in_arena_out = 1 when the
+ * buffer came from the registered arena.  RDEV_E_NOMEM if the chosen allocator is full. */
+rdev_status rdev_tracer_alloc(rdev_tracer_t *tr, uint32_t node_id, uint64_t bytes, void **ptr_out,
+                              uint32_t *alloc_index_out, uint32_t *in_arena_out);
+/* Give a buffer back before the iteration ends (its address may be handed out again). */
+rdev_status rdev_tracer_free(rdev_tracer_t *tr, void *ptr);
+/* The lookup of section 3.4 alone, nothing moves: the buffer at `ptr` is being
+ * transferred; in the tracing iteration its allocation site is added to S.
+ * *registered_out = 1 when the buffer lies in the registered arena.  (Works on a
+ * host-only device.) */
+rdev_status rdev_tracer_mark_sent(rdev_tracer_t *tr, const void *ptr, uint32_t *registered_out);
+/* Send static tensor `tensor_id` of `plan` from the buffer at `ptr` (a pointer
+ * returned by rdev_tracer_alloc).  In the tracing iteration the buffer's
+ * allocation site is added to S.  If the buffer is in registered memory this is
+ * a zero-copy rdev_write_batch of one tensor; otherwise a registered staging
+ * region is allocated in the arena, the tensor copied into it and written from
+ * there (section 5.1, analysis switched off).  *copied_out = 1 in the second case. */
+rdev_status rdev_tracer_send(rdev_tracer_t *tr, rdev_plan_t *plan, uint32_t tensor_id, const void *ptr,
+                             uint32_t seq, void *stream, uint32_t *copied_out);
+/* The set S, in insertion order. */
+rdev_status rdev_tracer_set_size(const rdev_tracer_t *tr, uint32_t *n_out);
+rdev_status rdev_tracer_set_get(const rdev_tracer_t *tr, uint32_t i, uint32_t *node_id_out, uint32_t *alloc_index_out);
+
 /* ---- measurement -------------------------------------------------------- */
 
 /* Time the batched copy kernel of whole-plan transfers (x == NULL) with HIP

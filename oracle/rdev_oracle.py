@@ -597,3 +597,102 @@ def gather_unique_rows(ids: np.ndarray, table: np.ndarray):
     """Rows of `table` touched by the mini-batch's token ids, ascending id, each once."""
     u = np.unique(np.asarray(ids).reshape(-1))
     return u.astype(np.int64), table[u]
+
+
+# ---------------------------------------------------------------------------
+# section 3.4: sender-side allocation-site tracing
+# ---------------------------------------------------------------------------
+class Tracer:
+    """The instrumented allocator of the sender's runtime.
+
+    First mini-batch: every allocation is recorded as address -> (node id, index
+    of the allocation within that node's execution); an allocation that reuses an
+    address replaces the older entry.  When a tensor is sent, its buffer address
+    is looked up and the allocation site found goes into the set S.  Later
+    mini-batches: an allocation whose site is in S is served from the registered
+    arena, all others from the ordinary (unregistered) pool.  A tensor sent from
+    the pool is first copied into a freshly allocated registered staging buffer.
+    """
+
+    def __init__(self, dev: Device, pool: np.ndarray, arena: int):
+        dev._arena(arena)
+        self.dev, self.pool, self.arena = dev, pool, arena
+        self.pool_alloc = RegionAllocator(pool.size)
+        self.iteration = 0
+        self.next_index: Dict[int, int] = {}
+        self.site_of: Dict[Tuple[str, int], Tuple[int, int]] = {}    # address -> allocation site
+        self.S: List[Tuple[int, int]] = []
+        self.live: Dict[Tuple[str, int], int] = {}                    # address -> bytes
+        self.staging: List[Tuple[int, int, int]] = []
+
+    def _release_all(self) -> None:
+        for (where, off), nb in self.live.items():
+            (self.dev.arenas[self.arena].alloc if where == "arena" else self.pool_alloc).release(off, nb)
+        self.live.clear()
+        for r in self.staging:
+            self.dev.free_region(r)
+        self.staging.clear()
+
+    def begin_iteration(self) -> None:
+        self._release_all()
+        self.next_index.clear()
+        self.iteration += 1
+
+    def alloc(self, node: int, nbytes: int) -> Tuple[str, int, int]:
+        """Returns (where, offset, allocation index)."""
+        if self.iteration == 0:
+            raise OracleError("state", "no iteration begun")
+        idx = self.next_index.get(node, 0)
+        where = "arena" if self.iteration > 1 and (node, idx) in self.S else "pool"
+        a = self.dev.arenas[self.arena].alloc if where == "arena" else self.pool_alloc
+        off = a.alloc(nbytes, 256)
+        self.next_index[node] = idx + 1
+        self.live[(where, off)] = nbytes
+        if self.iteration == 1:
+            self.site_of[(where, off)] = (node, idx)
+        return where, off, idx
+
+    def free(self, where: str, off: int) -> None:
+        nb = self.live.pop((where, off), None)
+        if nb is None:
+            raise OracleError("inval", "not a live buffer")
+        (self.dev.arenas[self.arena].alloc if where == "arena" else self.pool_alloc).release(off, nb)
+
+    def buffer(self, where: str, off: int, nbytes: int) -> np.ndarray:
+        mem = self.dev.arenas[self.arena].mem if where == "arena" else self.pool
+        return mem[off:off + nbytes]
+
+    def send(self, pl: Plan, tensor_id: int, where: str, off: int, seq: int) -> bool:
+        """Returns True when the tensor had to be staged (copied)."""
+        p = pl.get(tensor_id)
+        if p.kind != STATIC:
+            raise OracleError("inval", "not a static tensor")
+        if (where, off) not in self.live:
+            raise OracleError("inval", "not a live buffer")
+        if self.live[(where, off)] < p.nbytes:
+            raise OracleError("range", "buffer smaller than the tensor")
+        copied = where != "arena"
+        src = (self.arena, off)
+        stage = None
+        if copied:
+            if p.nbytes:
+                stage = self.dev.alloc_region(self.arena, p.nbytes, 256)
+                src = (self.arena, stage[1])
+            else:
+                src = (self.arena, 0)
+        try:
+            _check_src(self.dev, src, p.nbytes)
+            _check_disjoint(src, (p.dst_arena, p.data_offset), p.nbytes)
+        except OracleError:
+            if stage:
+                self.dev.free_region(stage)
+            raise
+        if self.iteration == 1:
+            site = self.site_of.get((where, off))
+            if site is not None and site not in self.S:
+                self.S.append(site)
+        if copied and p.nbytes:
+            self.staging.append(stage)
+            self.dev._store("stage", tensor_id, self.arena, stage[1], self.pool[off:off + p.nbytes].copy())
+        static_write(self.dev, pl, {tensor_id: src}, seq, [tensor_id])
+        return copied

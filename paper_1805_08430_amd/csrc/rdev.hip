@@ -137,6 +137,22 @@ struct rdev_plan_s {
     uint32_t n_pack_blocks = 0, n_stage_blocks = 0, n_unpack_blocks = 0;
 };
 
+struct rdev_tracer_s {
+    rdev_device_t *dev = nullptr;
+    uint8_t *pool_base = nullptr;
+    uint64_t pool_bytes = 0;
+    uint32_t arena_id = 0;
+    rdev::RegionAllocator pool;
+    uint32_t iteration = 0;                                             // 0 = none begun yet
+    std::map<uint32_t, uint32_t> next_index;                            // node -> allocations so far this iteration
+    std::map<uintptr_t, std::pair<uint32_t, uint32_t>> site_of;         // address -> (node, index), last writer wins
+    std::vector<std::pair<uint32_t, uint32_t>> S;                       // insertion order
+    std::map<std::pair<uint32_t, uint32_t>, bool> in_S;
+    struct Buf { uint64_t offset, bytes; bool arena; };
+    std::map<uintptr_t, Buf> live;                                      // buffers handed out, by address
+    std::vector<rdev_region> staging;                                   // staging regions of this iteration
+};
+
 namespace {
 
 rdev_status arena_of(rdev_device_t *dev, uint32_t id, Arena **out) {
@@ -1112,6 +1128,168 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
         std::vector<std::pair<uint32_t *, uint32_t>> f{{arena_flag, widx}};
         RDEV_TRY(launch_inline_flags(plan, f, 0u, false, s));
     }
+    return RDEV_OK;
+}
+
+// ---- allocation-site tracing (section 3.4) ----
+
+static void tracer_release_all(rdev_tracer_t *tr) {
+    std::string ignore;
+    Arena &ar = tr->dev->arenas[tr->arena_id];
+    for (auto &kv : tr->live) {
+        if (kv.second.arena) ar.alloc.release(kv.second.offset, kv.second.bytes, ignore);
+        else tr->pool.release(kv.second.offset, kv.second.bytes, ignore);
+    }
+    tr->live.clear();
+    for (const rdev_region &r : tr->staging) ar.alloc.release(r.offset, r.bytes, ignore);
+    tr->staging.clear();
+}
+
+rdev_status rdev_tracer_open(rdev_device_t *dev, void *pool_base, uint64_t pool_bytes, uint32_t arena_id,
+                             rdev_tracer_t **out) {
+    if (!dev || !out || !pool_base || !pool_bytes) return fail(RDEV_E_INVAL, "NULL argument");
+    Arena *a;
+    RDEV_TRY(arena_of(dev, arena_id, &a));
+    if ((uintptr_t)pool_base & 255) return fail(RDEV_E_ALIGN, "pool base must be 256-byte aligned");
+    SrcLoc loc;
+    if (locate(dev, pool_base, pool_bytes, &loc) == RDEV_OK || locate(dev, pool_base, 1, &loc) == RDEV_OK)
+        return fail(RDEV_E_OVERLAP, "the ordinary pool must not be registered memory");
+    rdev_tracer_t *tr = new rdev_tracer_t();
+    tr->dev = dev;
+    tr->pool_base = (uint8_t *)pool_base;
+    tr->pool_bytes = pool_bytes;
+    tr->arena_id = arena_id;
+    tr->pool = rdev::RegionAllocator(pool_bytes);
+    *out = tr;
+    return RDEV_OK;
+}
+
+rdev_status rdev_tracer_close(rdev_tracer_t *tr) {
+    if (!tr) return fail(RDEV_E_INVAL, "NULL argument");
+    tracer_release_all(tr);
+    delete tr;
+    return RDEV_OK;
+}
+
+rdev_status rdev_tracer_begin_iteration(rdev_tracer_t *tr) {
+    if (!tr) return fail(RDEV_E_INVAL, "NULL argument");
+    tracer_release_all(tr);
+    tr->next_index.clear();
+    tr->iteration++;
+    return RDEV_OK;
+}
+
+rdev_status rdev_tracer_alloc(rdev_tracer_t *tr, uint32_t node_id, uint64_t bytes, void **ptr_out,
+                              uint32_t *alloc_index_out, uint32_t *in_arena_out) {
+    if (!tr || !ptr_out) return fail(RDEV_E_INVAL, "NULL argument");
+    if (!tr->iteration) return fail(RDEV_E_STATE, "no iteration begun");
+    if (!bytes) return fail(RDEV_E_INVAL, "bytes must be positive");
+    const uint32_t idx = tr->next_index[node_id];
+    const bool arena = tr->iteration > 1 && tr->in_S.count({node_id, idx});
+    uint64_t off;
+    std::string err;
+    Arena &ar = tr->dev->arenas[tr->arena_id];
+    rdev_status st = arena ? ar.alloc.alloc(bytes, 256, &off, err) : tr->pool.alloc(bytes, 256, &off, err);
+    if (st != RDEV_OK) return fail(st, std::string(arena ? "registered arena: " : "ordinary pool: ") + err);
+    tr->next_index[node_id] = idx + 1;
+    uint8_t *p = (arena ? ar.base : tr->pool_base) + off;
+    tr->live[(uintptr_t)p] = rdev_tracer_s::Buf{off, bytes, arena};
+    if (tr->iteration == 1) tr->site_of[(uintptr_t)p] = {node_id, idx};      // last writer wins
+    *ptr_out = p;
+    if (alloc_index_out) *alloc_index_out = idx;
+    if (in_arena_out) *in_arena_out = arena ? 1 : 0;
+    return RDEV_OK;
+}
+
+rdev_status rdev_tracer_free(rdev_tracer_t *tr, void *ptr) {
+    if (!tr) return fail(RDEV_E_INVAL, "NULL argument");
+    auto it = tr->live.find((uintptr_t)ptr);
+    if (it == tr->live.end()) return fail(RDEV_E_INVAL, "not a live buffer of this tracer");
+    std::string err;
+    if (it->second.arena) tr->dev->arenas[tr->arena_id].alloc.release(it->second.offset, it->second.bytes, err);
+    else tr->pool.release(it->second.offset, it->second.bytes, err);
+    tr->live.erase(it);
+    return RDEV_OK;
+}
+
+rdev_status rdev_tracer_mark_sent(rdev_tracer_t *tr, const void *ptr, uint32_t *registered_out) {
+    if (!tr || !ptr) return fail(RDEV_E_INVAL, "NULL argument");
+    auto it = tr->live.find((uintptr_t)ptr);
+    if (it == tr->live.end()) return fail(RDEV_E_INVAL, "not a live buffer of this tracer");
+    if (tr->iteration == 1) {
+        auto site = tr->site_of.find((uintptr_t)ptr);
+        if (site != tr->site_of.end() && !tr->in_S.count(site->second)) {
+            tr->in_S[site->second] = true;
+            tr->S.push_back(site->second);
+        }
+    }
+    if (registered_out) *registered_out = it->second.arena ? 1 : 0;
+    return RDEV_OK;
+}
+
+rdev_status rdev_tracer_send(rdev_tracer_t *tr, rdev_plan_t *plan, uint32_t tensor_id, const void *ptr, uint32_t seq,
+                             void *stream, uint32_t *copied_out) {
+    if (!tr || !plan || plan->dev != tr->dev || !ptr) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
+    if (!seq) return fail(RDEV_E_INVAL, "seq must be >= 1");
+    RDEV_TRY(require_gpu(tr->dev));
+    uint32_t idx;
+    RDEV_TRY(index_of(plan, tensor_id, &idx));
+    const rdev_placement &p = plan->pl[idx];
+    if (p.kind != RDEV_STATIC) return fail(RDEV_E_INVAL, "not a static tensor");
+    auto it = tr->live.find((uintptr_t)ptr);
+    if (it == tr->live.end()) return fail(RDEV_E_INVAL, "not a live buffer of this tracer");
+    if (it->second.bytes < p.bytes) return fail(RDEV_E_RANGE, "buffer is smaller than the tensor");
+    hipStream_t s = (hipStream_t)stream;
+    const void *src = ptr;
+    uint32_t copied = 0;
+    rdev_region stage{};
+    if (!it->second.arena) {
+        // not registered: stage through a fresh registered buffer
+        if (p.bytes) {
+            uint64_t off;
+            std::string err;
+            rdev_status st = tr->dev->arenas[tr->arena_id].alloc.alloc(p.bytes, 256, &off, err);
+            if (st != RDEV_OK) return fail(st, "staging buffer: " + err);
+            stage = rdev_region{tr->arena_id, 0, off, p.bytes};
+            src = tr->dev->arenas[tr->arena_id].base + off;
+        } else {
+            src = tr->dev->arenas[tr->arena_id].base;
+        }
+        copied = 1;
+    }
+    // validate the write before anything is enqueued
+    ResolvedStatic r;
+    rdev_status st = resolve_static(plan, idx, src, &r);
+    if (st == RDEV_OK && (plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && static_ready(plan, idx))
+        st = fail(RDEV_E_BUSY, "tensor " + std::to_string(tensor_id) + " has not been consumed");
+    if (st != RDEV_OK) {
+        std::string ignore;
+        if (stage.bytes) tr->dev->arenas[tr->arena_id].alloc.release(stage.offset, stage.bytes, ignore);
+        return st;
+    }
+    RDEV_TRY(rdev_tracer_mark_sent(tr, ptr, nullptr));
+    if (copied && p.bytes) {
+        tr->staging.push_back(stage);
+        std::vector<ResolvedStatic> one{ResolvedStatic{idx, (const uint8_t *)ptr, (uint8_t *)const_cast<void *>(src), p.bytes}};
+        RDEV_TRY(launch_inline_copies(plan, one, s));
+    }
+    std::vector<std::pair<uint32_t, const void *>> list{{idx, src}};
+    RDEV_TRY(transfer_static_list(plan, list, seq, s));
+    if (copied_out) *copied_out = copied;
+    return RDEV_OK;
+}
+
+rdev_status rdev_tracer_set_size(const rdev_tracer_t *tr, uint32_t *n_out) {
+    if (!tr || !n_out) return fail(RDEV_E_INVAL, "NULL argument");
+    *n_out = (uint32_t)tr->S.size();
+    return RDEV_OK;
+}
+
+rdev_status rdev_tracer_set_get(const rdev_tracer_t *tr, uint32_t i, uint32_t *node_id_out, uint32_t *alloc_index_out) {
+    if (!tr || !node_id_out || !alloc_index_out) return fail(RDEV_E_INVAL, "NULL argument");
+    if (i >= tr->S.size()) return fail(RDEV_E_INVAL, "index out of range");
+    *node_id_out = tr->S[i].first;
+    *alloc_index_out = tr->S[i].second;
     return RDEV_OK;
 }
 

@@ -94,6 +94,16 @@ SYMBOLS = {
     "rdev_write_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, C.c_uint32, _P]),
     "rdev_read_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
     "rdev_poll": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, C.POINTER(Meta), _P]),
+    "rdev_tracer_open": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, C.POINTER(_P)]),
+    "rdev_tracer_close": (C.c_int32, [_P]),
+    "rdev_tracer_begin_iteration": (C.c_int32, [_P]),
+    "rdev_tracer_alloc": (C.c_int32, [_P, C.c_uint32, C.c_uint64, C.POINTER(_P), C.POINTER(C.c_uint32),
+                                      C.POINTER(C.c_uint32)]),
+    "rdev_tracer_free": (C.c_int32, [_P, _P]),
+    "rdev_tracer_mark_sent": (C.c_int32, [_P, _P, C.POINTER(C.c_uint32)]),
+    "rdev_tracer_send": (C.c_int32, [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.POINTER(C.c_uint32)]),
+    "rdev_tracer_set_size": (C.c_int32, [_P, C.POINTER(C.c_uint32)]),
+    "rdev_tracer_set_get": (C.c_int32, [_P, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]),
     "rdev_plan_profile": (C.c_int32, [_P, C.c_uint32, C.c_uint32]),
     "rdev_plan_profile_read": (C.c_int32, [_P, C.POINTER(C.c_float), C.c_uint32, C.POINTER(C.c_uint32)]),
 }
@@ -247,6 +257,56 @@ def rdev_poll(dev: int, plan: int, tensor_id: int = ALL_TENSORS, poll_flags: int
     if want_meta:
         return ready, (m if ready else None)
     return ready
+
+
+def rdev_tracer_open(dev: int, pool_base: int, pool_bytes: int, arena_id: int) -> int:
+    h = _P()
+    _check(lib().rdev_tracer_open(dev, pool_base, pool_bytes, arena_id, C.byref(h)))
+    return h.value
+
+
+def rdev_tracer_close(tr: int) -> None:
+    _check(lib().rdev_tracer_close(tr))
+
+
+def rdev_tracer_begin_iteration(tr: int) -> None:
+    _check(lib().rdev_tracer_begin_iteration(tr))
+
+
+def rdev_tracer_alloc(tr: int, node_id: int, nbytes: int):
+    """Returns (device pointer, allocation index, in_arena)."""
+    p, idx, ar = _P(), C.c_uint32(), C.c_uint32()
+    _check(lib().rdev_tracer_alloc(tr, node_id, nbytes, C.byref(p), C.byref(idx), C.byref(ar)))
+    return p.value, idx.value, bool(ar.value)
+
+
+def rdev_tracer_free(tr: int, ptr: int) -> None:
+    _check(lib().rdev_tracer_free(tr, ptr))
+
+
+def rdev_tracer_mark_sent(tr: int, ptr: int) -> bool:
+    """Returns True when the buffer lies in registered memory."""
+    r = C.c_uint32()
+    _check(lib().rdev_tracer_mark_sent(tr, ptr, C.byref(r)))
+    return bool(r.value)
+
+
+def rdev_tracer_send(tr: int, plan: int, tensor_id: int, ptr: int, seq: int = 1, stream: int = 0) -> bool:
+    """Returns True when the tensor was staged (copied) before the write."""
+    c = C.c_uint32()
+    _check(lib().rdev_tracer_send(tr, plan, tensor_id, ptr, seq, stream or None, C.byref(c)))
+    return bool(c.value)
+
+
+def rdev_tracer_set(tr: int):
+    n = C.c_uint32()
+    _check(lib().rdev_tracer_set_size(tr, C.byref(n)))
+    out = []
+    for i in range(n.value):
+        a, b = C.c_uint32(), C.c_uint32()
+        _check(lib().rdev_tracer_set_get(tr, i, C.byref(a), C.byref(b)))
+        out.append((a.value, b.value))
+    return out
 
 
 def rdev_plan_profile(plan: int, max_samples: int, every: int = 1) -> None:
