@@ -194,6 +194,46 @@ def tracing_leg(R, torch, dev, wl, s, spin, iters=20):
             "traced_over_steady": round(times[0] / steady, 3)}
 
 
+def consumer_leg(R, torch, W, dev, wl, opts, s, spin, iters=20):
+    """Sections 4 / 5.1: one send per tensor, each received tensor consumed by a
+    reduce_max kernel on a second stream.  (a) one event at the end of the whole
+    set, then all consumers; (b) polling-async: per-tensor flags polled on the
+    host, a tensor's consumer starts while later tensors are still in flight."""
+    images = W.fill_sources(wl, 0)
+    ts = TransferSet(R, torch, W, dev, wl, images, opts)
+    del images
+    ids = [i for i, t in enumerate(wl.tensors) if t.is_static and t.nbytes % 4 == 0]
+    xs = [[R.make_xfer(i)] for i in ids]
+    res = torch.zeros(len(ids) * 24 + 16, dtype=torch.uint8, device="cuda:0")
+    base = (res.data_ptr() + 15) // 16 * 16
+    cons = torch.cuda.Stream()
+    c = cons.cuda_stream
+    seq = 0
+    t_event, t_async = [], []
+    for it in range(iters + 2):
+        for variant in ("event", "async"):
+            torch.cuda.synchronize()
+            seq += 1
+            t0 = time.perf_counter()
+            for x in xs:
+                R.rdev_write_batch(dev, ts.plan, x, R.ZEROCOPY, seq, s)
+            if variant == "event":
+                spin(lambda: all(R.rdev_poll(dev, ts.plan, i) for i in ids))
+                for k, i in enumerate(ids):
+                    R.rdev_poll(dev, ts.plan, i, R.POLL_CONSUME, s)
+                    R.rdev_consume_reduce_max(dev, ts.plan, i, 0, base + 24 * k, c)
+            else:
+                ok, _ = R.rdev_recv_polling_async(dev, ts.plan, ids, base, s, c)
+                assert ok
+            cons.synchronize()
+            torch.cuda.synchronize()
+            (t_event if variant == "event" else t_async).append((time.perf_counter() - t0) * 1e6)
+    ts.close()
+    med = lambda v: sorted(v[2:])[len(v[2:]) // 2]
+    return {"sends_per_iteration": len(ids), "end_of_set_event_us": round(med(t_event), 1),
+            "polling_async_us": round(med(t_async), 1), "gain": round(med(t_event) / med(t_async), 3)}
+
+
 def cpu_baseline(wl_name: str, seconds: float):
     """The CPU checker's static transfer on the same workload, as it stands."""
     import numpy as np
@@ -384,6 +424,7 @@ def main():
             ts.close()
         del msets
         out["tracing"] = tracing_leg(R, torch, dev, wl, s, spin)
+        out["consumer_overlap"] = consumer_leg(R, torch, W, dev, wl, opts, s, spin)
     if a.calibrate:
         nb = 256 << 20
         x = torch.ones(nb, dtype=torch.uint8, device="cuda:0")

@@ -258,6 +258,39 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
 rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
                       uint32_t poll_flags, rdev_meta *meta_out, void *stream);
 
+/* ---- receiver-side consumer (sections 4 and 5.1) -------------------------- */
+
+/* Result of the device-side consumer; lives in device memory. */
+typedef struct {
+    uint32_t status;        /* 0 = reduced; 1 = the flag was not seen within max_spins polls */
+    uint32_t seen_flag;     /* flag value the kernel saw (0 when it did not wait) */
+    float    max;           /* maximum of the fp32 elements; NaNs are skipped, -0 < +0, empty or all-NaN = -inf */
+    uint32_t _arrivals;     /* internal */
+    uint64_t word_sum;      /* sum of the payload's 32-bit words modulo 2^64 */
+} rdev_consume_result;
+
+/* The light consumer of the paper's send/receive micro-benchmark (reduce_max,
+ * section 5.1) for one static tensor whose size is a multiple of 4 bytes.
+ * With max_spins > 0 a small grid (64 workgroups at most: waiting workgroups
+ * occupy compute units, the cost section 3.5 warns of) first waits until the tensor's
+ * in-arena flag is non-zero - acquire loads, at most max_spins of them per
+ * workgroup - and then reduces the payload.  max_spins == 0: do not look at the
+ * flag at all (the caller has polled it on the host).  out: device pointer, 8-byte
+ * aligned; written by kernels on `stream`.  Never waits forever. */
+rdev_status rdev_consume_reduce_max(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id, uint32_t max_spins,
+                                    rdev_consume_result *out, void *stream);
+
+/* Polling-async reception (section 4): the listed static tensors form a ready
+ * queue; the head is polled on the host; if its flag is not set it goes back to
+ * the tail, otherwise the flag is consumed (cleared on flag_stream, the stream of
+ * the deliveries) and its consumer kernel is launched on consumer_stream, writing
+ * out[i] for tensor_ids[i].  Returns RDEV_OK when the queue is empty,
+ * RDEV_NOT_READY after max_polls failed polls in total.  *polls_out (may be NULL)
+ * = polls made. */
+rdev_status rdev_recv_polling_async(rdev_device_t *dev, rdev_plan_t *plan, const uint32_t *tensor_ids, uint32_t n,
+                                    rdev_consume_result *out, void *flag_stream, void *consumer_stream,
+                                    uint64_t max_polls, uint64_t *polls_out);
+
 /* ---- sender-side allocation-site tracing (section 3.4) ------------------- */
 
 /* A tensor can only be sent without a copy if its buffer was allocated in

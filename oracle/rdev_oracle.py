@@ -696,3 +696,29 @@ class Tracer:
             self.dev._store("stage", tensor_id, self.arena, stage[1], self.pool[off:off + p.nbytes].copy())
         static_write(self.dev, pl, {tensor_id: src}, seq, [tensor_id])
         return copied
+
+
+# ---------------------------------------------------------------------------
+# section 5.1: the receiver's light consumer (reduce_max) of the micro-benchmark
+# ---------------------------------------------------------------------------
+def consume_reduce_max(dev: Device, pl: Plan, tensor_id: int, from_offset: Optional[int] = None):
+    """(max, word_sum) of a delivered static tensor read as 32-bit words:
+    max over the fp32 values that are not NaN, with -0 below +0, -inf when
+    nothing is left; word_sum = sum of the words modulo 2^64."""
+    p = pl.get(tensor_id)
+    if p.kind != STATIC or p.nbytes % 4:
+        raise OracleError("inval", "consumer takes static tensors of 32-bit elements")
+    off = p.data_offset if from_offset is None else from_offset
+    words = dev.arenas[p.dst_arena].mem[off:off + p.nbytes].copy().view("<u4")
+    word_sum = 0
+    for chunk in np.array_split(words, max(1, words.size // (1 << 20))):
+        word_sum = (word_sum + int(chunk.astype(np.uint64).sum(dtype=np.uint64))) % (1 << 64)
+    vals = words.view(np.float32)
+    vals = vals[~np.isnan(vals)]
+    if vals.size == 0:
+        return np.float32(-np.inf), word_sum
+    mx = vals.max()
+    if mx == 0:
+        plus_zero = bool((vals.view("<u4") == 0).any())
+        mx = np.float32(0.0) if plus_zero else np.float32(-0.0)
+    return np.float32(mx), word_sum

@@ -41,8 +41,8 @@ struct InlineEnt {
     const uint8_t *src;
     uint8_t *dst;
     uint64_t bytes;
-    uint32_t first_block;
-    uint32_t _pad;
+    uint32_t first_block;   // first workgroup of this transfer; it owns 8 * per_xcd workgroups
+    uint32_t per_xcd;       // ceil(chunks / 8)
 };
 struct InlineBatch {
     InlineEnt e[kInlineMax];
@@ -148,7 +148,10 @@ __global__ __launch_bounds__(kBlockThreads) void copy_inline_kernel(InlineBatch 
     uint32_t k = 0;
     for (uint32_t i = 1; i < b.n; ++i)
         if (blockIdx.x >= b.e[i].first_block) k = i;
-    const uint64_t off = (uint64_t)(blockIdx.x - b.e[k].first_block) * b.chunk;
+    // same XCD-contiguous order as the table: workgroup j of a transfer takes chunk (j % 8) * per_xcd + j / 8
+    const uint32_t j = blockIdx.x - b.e[k].first_block;
+    const uint64_t off = ((uint64_t)(j % kXcds) * b.e[k].per_xcd + j / kXcds) * b.chunk;
+    if (off >= b.e[k].bytes) return;
     const uint64_t rem = b.e[k].bytes - off;
     const uint32_t n = rem < b.chunk ? (uint32_t)rem : b.chunk;
     copy_span(b.e[k].src + off, b.e[k].dst + off, n, threadIdx.x, kBlockThreads);
@@ -270,6 +273,90 @@ __global__ void rpc_flag_kernel(const FlagEnt *__restrict__ ents, uint8_t *const
         __hip_atomic_store(ents[i].arena_flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (i == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// ---- receiver-side consumer (sections 4, 5.1) ----
+
+constexpr uint32_t kConsumeThreads = 256;
+constexpr uint32_t kConsumeMaxBlocks = 64;         // when the kernel waits for the flag on the device
+constexpr uint32_t kConsumeMaxBlocksNoWait = 2048; // when the host has seen the flag already
+
+// order-preserving map of non-NaN floats to unsigned (and -0 < +0)
+__device__ __forceinline__ uint32_t f2ord(uint32_t bits) { return bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u); }
+__device__ __forceinline__ uint32_t ord2f(uint32_t o) { return o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu); }
+constexpr uint32_t kOrdNegInf = 0x007FFFFFu;     // f2ord(bits of -inf = 0xFF800000)
+
+__global__ void consume_init_kernel(rdev_consume_result *out) {
+    if (threadIdx.x == 0) {
+        out->status = 1;
+        out->seen_flag = 0;
+        ((uint32_t *)&out->max)[0] = kOrdNegInf;     // holds the ordered key until the last workgroup converts it
+        out->_arrivals = 0;
+        out->word_sum = 0;
+    }
+}
+
+__global__ __launch_bounds__(kConsumeThreads) void consume_reduce_max_kernel(const uint32_t *flag, const uint8_t *payload,
+                                                                             uint64_t bytes, uint32_t max_spins,
+                                                                             rdev_consume_result *out) {
+    __shared__ uint32_t s_seen;
+    __shared__ uint32_t s_max[kConsumeThreads / 64];
+    __shared__ uint64_t s_sum[kConsumeThreads / 64];
+    uint32_t seen = 0;
+    if (max_spins) {
+        if (threadIdx.x == 0) {
+            uint32_t v = 0;
+            for (uint32_t k = 0; k < max_spins; ++k) {
+                v = __hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                if (v) break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            s_seen = v;
+        }
+        __syncthreads();
+        seen = s_seen;
+        if (!seen) return;                              // status stays 1: every workgroup leaves
+    }
+    const uint64_t nvec = bytes >> 4;
+    const v4u *p = (const v4u *)payload;
+    uint32_t m = kOrdNegInf;
+    uint64_t sum = 0;
+    auto take = [&](uint32_t w) {
+        sum += w;
+        if ((w & 0x7FFFFFFFu) <= 0x7F800000u) {         // not a NaN
+            const uint32_t o = f2ord(w);
+            m = o > m ? o : m;
+        }
+    };
+    for (uint64_t i = (uint64_t)blockIdx.x * kConsumeThreads + threadIdx.x; i < nvec; i += (uint64_t)gridDim.x * kConsumeThreads) {
+        const v4u v = __builtin_nontemporal_load(p + i);
+        take(v.x); take(v.y); take(v.z); take(v.w);
+    }
+    if (blockIdx.x == 0) {                               // up to three trailing words
+        const uint32_t tail = (uint32_t)((bytes & 15) >> 2);
+        if (threadIdx.x < tail) take(((const uint32_t *)payload)[nvec * 4 + threadIdx.x]);
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t om = __shfl_down(m, off, 64);
+        const uint64_t os = __shfl_down(sum, off, 64);
+        m = om > m ? om : m;
+        sum += os;
+    }
+    if ((threadIdx.x & 63) == 0) { s_max[threadIdx.x >> 6] = m; s_sum[threadIdx.x >> 6] = sum; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (uint32_t w = 1; w < kConsumeThreads / 64; ++w) { m = s_max[w] > m ? s_max[w] : m; sum += s_sum[w]; }
+        __hip_atomic_fetch_max((uint32_t *)&out->max, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add((unsigned long long *)&out->word_sum, (unsigned long long)sum, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + 1 == gridDim.x) {                     // last workgroup: publish
+            const uint32_t key = __hip_atomic_load((uint32_t *)&out->max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ((uint32_t *)&out->max)[0] = ord2f(key);
+            out->seen_flag = seen;
+            out->status = 0;
+        }
+    }
 }
 
 }  // namespace rdev

@@ -297,13 +297,14 @@ rdev_status launch_inline_copies(rdev_plan_t *plan, const std::vector<ResolvedSt
         b.chunk = (uint32_t)chunk;
         uint64_t blocks = 0;
         while (i < v.size() && b.n < rdev::kInlineMax) {
-            const uint64_t nb = (v[i].bytes + chunk - 1) / chunk;
+            const uint64_t per = ((v[i].bytes + chunk - 1) / chunk + rdev::kXcds - 1) / rdev::kXcds;
+            const uint64_t nb = per * rdev::kXcds;
             if (blocks + nb > 0x7fffffffull) {
                 if (b.n == 0) return fail(RDEV_E_INVAL, "transfer too large for one launch with this chunk size");
                 break;
             }
             if (nb) {
-                b.e[b.n] = rdev::InlineEnt{v[i].src, v[i].dst, v[i].bytes, (uint32_t)blocks, 0};
+                b.e[b.n] = rdev::InlineEnt{v[i].src, v[i].dst, v[i].bytes, (uint32_t)blocks, (uint32_t)per};
                 b.n++;
                 blocks += nb;
             }
@@ -1129,6 +1130,76 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
         RDEV_TRY(launch_inline_flags(plan, f, 0u, false, s));
     }
     return RDEV_OK;
+}
+
+// ---- receiver-side consumer (sections 4, 5.1) ----
+
+static rdev_status consume_checked(rdev_plan_t *plan, uint32_t idx, uint32_t max_spins, rdev_consume_result *out,
+                                   hipStream_t s) {
+    const rdev_placement &p = plan->pl[idx];
+    hipLaunchKernelGGL(rdev::consume_init_kernel, dim3(1), dim3(64), 0, s, out);
+    RDEV_TRY(launch_check("consume_init_kernel"));
+    const uint64_t per_block = (uint64_t)rdev::kConsumeThreads * 16 * 16;        // 64 KiB of payload per workgroup pass
+    const uint32_t cap = max_spins ? rdev::kConsumeMaxBlocks : rdev::kConsumeMaxBlocksNoWait;
+    uint32_t grid = (uint32_t)std::min<uint64_t>(cap, (p.bytes + per_block - 1) / per_block);
+    if (!grid) grid = 1;
+    hipLaunchKernelGGL(rdev::consume_reduce_max_kernel, dim3(grid), dim3(rdev::kConsumeThreads), 0, s,
+                       (const uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset),
+                       (const uint8_t *)arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, max_spins, out);
+    return launch_check("consume_reduce_max_kernel");
+}
+
+static rdev_status consume_validate(rdev_plan_t *plan, uint32_t tensor_id, const rdev_consume_result *out, uint32_t *idx) {
+    RDEV_TRY(index_of(plan, tensor_id, idx));
+    const rdev_placement &p = plan->pl[*idx];
+    if (p.kind != RDEV_STATIC) return fail(RDEV_E_INVAL, "the consumer takes static tensors");
+    if (p.bytes % 4) return fail(RDEV_E_INVAL, "the consumer reduces 32-bit elements: bytes must be a multiple of 4");
+    if (!out || ((uintptr_t)out & 7)) return fail(RDEV_E_ALIGN, "result pointer must be 8-byte aligned device memory");
+    return RDEV_OK;
+}
+
+rdev_status rdev_consume_reduce_max(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id, uint32_t max_spins,
+                                    rdev_consume_result *out, void *stream) {
+    if (!dev || !plan || plan->dev != dev) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
+    RDEV_TRY(require_gpu(dev));
+    uint32_t idx;
+    RDEV_TRY(consume_validate(plan, tensor_id, out, &idx));
+    return consume_checked(plan, idx, max_spins, out, (hipStream_t)stream);
+}
+
+rdev_status rdev_recv_polling_async(rdev_device_t *dev, rdev_plan_t *plan, const uint32_t *tensor_ids, uint32_t n,
+                                    rdev_consume_result *out, void *flag_stream, void *consumer_stream,
+                                    uint64_t max_polls, uint64_t *polls_out) {
+    if (!dev || !plan || plan->dev != dev || (!tensor_ids && n)) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
+    RDEV_TRY(require_gpu(dev));
+    std::vector<uint32_t> idx(n);
+    for (uint32_t i = 0; i < n; ++i) RDEV_TRY(consume_validate(plan, tensor_ids[i], out + i, &idx[i]));
+    std::vector<uint32_t> queue(n);                 // positions 0..n-1 of the caller's list, in ready-queue order
+    for (uint32_t i = 0; i < n; ++i) queue[i] = i;
+    size_t head = 0;
+    uint64_t polls = 0, failed = 0;
+    rdev_status result = RDEV_OK;
+    while (head < queue.size()) {
+        const uint32_t i = queue[head++];
+        ++polls;
+        if (!static_ready(plan, idx[i])) {
+            if (++failed >= max_polls) { result = RDEV_NOT_READY; break; }
+            queue.push_back(i);                     // back to the tail of the ready queue
+            if (head > 4096 && head * 2 > queue.size()) {   // keep the vector from growing without bound
+                queue.erase(queue.begin(), queue.begin() + head);
+                head = 0;
+            }
+            continue;
+        }
+        // success: consume the flag, the op turns asynchronous
+        static_consume(plan, idx[i]);
+        const rdev_placement &p = plan->pl[idx[i]];
+        std::vector<std::pair<uint32_t *, uint32_t>> f{{(uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset), 2 * idx[i]}};
+        RDEV_TRY(launch_inline_flags(plan, f, 0u, false, (hipStream_t)flag_stream));
+        RDEV_TRY(consume_checked(plan, idx[i], 0, out + i, (hipStream_t)consumer_stream));
+    }
+    if (polls_out) *polls_out = polls;
+    return result;
 }
 
 // ---- allocation-site tracing (section 3.4) ----

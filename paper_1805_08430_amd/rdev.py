@@ -64,6 +64,11 @@ class Xfer(C.Structure):
                 ("_pad", C.c_uint32), ("dims", C.c_int64 * MAX_DIMS)]
 
 
+class ConsumeResult(C.Structure):
+    _fields_ = [("status", C.c_uint32), ("seen_flag", C.c_uint32), ("max", C.c_float), ("_arrivals", C.c_uint32),
+                ("word_sum", C.c_uint64)]
+
+
 class RdevError(RuntimeError):
     def __init__(self, status: int, msg: str):
         super().__init__(f"{_ERR_NAMES.get(status, status)}: {msg}")
@@ -94,6 +99,9 @@ SYMBOLS = {
     "rdev_write_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, C.c_uint32, _P]),
     "rdev_read_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
     "rdev_poll": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, C.POINTER(Meta), _P]),
+    "rdev_consume_reduce_max": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, _P, _P]),
+    "rdev_recv_polling_async": (C.c_int32, [_P, _P, C.POINTER(C.c_uint32), C.c_uint32, _P, _P, _P, C.c_uint64,
+                                            C.POINTER(C.c_uint64)]),
     "rdev_tracer_open": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, C.POINTER(_P)]),
     "rdev_tracer_close": (C.c_int32, [_P]),
     "rdev_tracer_begin_iteration": (C.c_int32, [_P]),
@@ -257,6 +265,20 @@ def rdev_poll(dev: int, plan: int, tensor_id: int = ALL_TENSORS, poll_flags: int
     if want_meta:
         return ready, (m if ready else None)
     return ready
+
+
+def rdev_consume_reduce_max(dev: int, plan: int, tensor_id: int, max_spins: int, out_ptr: int, stream: int = 0) -> None:
+    _check(lib().rdev_consume_reduce_max(dev, plan, tensor_id, max_spins, out_ptr, stream or None))
+
+
+def rdev_recv_polling_async(dev: int, plan: int, tensor_ids: Sequence[int], out_ptr: int, flag_stream: int = 0,
+                            consumer_stream: int = 0, max_polls: int = 1 << 40):
+    """Returns (all_received, polls made)."""
+    arr = (C.c_uint32 * max(len(tensor_ids), 1))(*tensor_ids)
+    polls = C.c_uint64()
+    st = _check(lib().rdev_recv_polling_async(dev, plan, arr, len(tensor_ids), out_ptr, flag_stream or None,
+                                              consumer_stream or None, max_polls, C.byref(polls)))
+    return st == OK, polls.value
 
 
 def rdev_tracer_open(dev: int, pool_base: int, pool_bytes: int, arena_id: int) -> int:
