@@ -341,6 +341,52 @@ rdev_status rdev_tracer_send(rdev_tracer_t *tr, rdev_plan_t *plan, uint32_t tens
 rdev_status rdev_tracer_set_size(const rdev_tracer_t *tr, uint32_t *n_out);
 rdev_status rdev_tracer_set_get(const rdev_tracer_t *tr, uint32_t i, uint32_t *node_id_out, uint32_t *alloc_index_out);
 
+/* ---- graph analysis: static shape inference (section 3.4, first step) ----- */
+
+/* A small dataflow graph: values (tensors on edges) are produced by inputs
+ * (placeholders with user-annotated shapes, variables) and by nodes with one
+ * output each; every node has a shape-inference function that gives the output
+ * shape from the input shapes.  Unknown dims (-1) propagate.  After inference,
+ * every value consumed in another partition than the one that produces it is a
+ * transferred tensor, and rdev_graph_transfers emits the rdev_tensor_desc list
+ * that rdev_plan classifies and places (static iff no dim is -1). */
+typedef struct rdev_graph_s rdev_graph_t;
+
+enum {
+    RDEV_OP_UNARY     = 0,  /* 1 input; output = input shape.  attrs: none */
+    RDEV_OP_BINARY    = 1,  /* 2 inputs, elementwise with broadcasting (trailing dims aligned, 1 stretches) */
+    RDEV_OP_MATMUL    = 2,  /* [.., m, k] x [k, n] -> [.., m, n].  attrs: transpose_a, transpose_b (of the last two dims) */
+    RDEV_OP_TRANSPOSE = 3,  /* attrs: the permutation */
+    RDEV_OP_RESHAPE   = 4,  /* attrs: target dims, at most one -1 (inferred when the element count is known) */
+    RDEV_OP_CONCAT    = 5,  /* >= 1 inputs.  attrs: axis */
+    RDEV_OP_REDUCE    = 6,  /* attrs: keepdims, then the reduced axes */
+    RDEV_OP_GATHER    = 7,  /* inputs: params [V, ...], ids [...] -> ids.shape + params.shape[1:] */
+    RDEV_OP_UNIQUE    = 8,  /* any shape -> [-1]: the count depends on the data */
+    RDEV_OP_CONV2D    = 9,  /* x [N,H,W,C], filter [kh,kw,C,O].  attrs: stride_h, stride_w, padding (0 valid, 1 same) */
+    RDEV_OP_GRAD      = 10, /* inputs: anything..., last = the value differentiated against -> its shape and type */
+    RDEV_OP_CAST      = 11  /* attrs: new element type */
+};
+
+rdev_status rdev_graph_open(rdev_graph_t **out);
+rdev_status rdev_graph_close(rdev_graph_t *g);
+/* A value that enters the graph in `partition` with an annotated shape (dims[i] == -1: unknown). */
+rdev_status rdev_graph_input(rdev_graph_t *g, uint32_t dtype, uint32_t ndims, const int64_t *dims, uint32_t partition,
+                             uint32_t *value_out);
+/* A node placed in `partition`; inputs are value ids created earlier (so insertion order is a topological order). */
+rdev_status rdev_graph_node(rdev_graph_t *g, uint32_t op, const uint32_t *inputs, uint32_t n_inputs,
+                            const int64_t *attrs, uint32_t n_attrs, uint32_t partition, uint32_t *value_out);
+/* Run every node's shape function.  RDEV_E_INVAL with the node named in rdev_last_error() when known dims contradict. */
+rdev_status rdev_graph_infer(rdev_graph_t *g);
+/* Inferred type and shape of a value (out->tensor_id = value id, out->dst_arena = its partition). */
+rdev_status rdev_graph_value(const rdev_graph_t *g, uint32_t value, rdev_tensor_desc *out);
+/* The tensors that cross partitions, ordered by (value id, consumer partition):
+ * out[i].tensor_id = i, out[i].dst_arena = partition_to_arena[consumer partition].
+ * values_out / dst_partitions_out (host arrays of cap entries, may be NULL) tell which value goes where.
+ * *n_out = number of transfers (also when cap is too small: then RDEV_E_NOMEM). */
+rdev_status rdev_graph_transfers(const rdev_graph_t *g, const uint32_t *partition_to_arena, uint32_t n_partitions,
+                                 rdev_tensor_desc *out, uint32_t *values_out, uint32_t *dst_partitions_out,
+                                 uint32_t cap, uint32_t *n_out);
+
 /* ---- measurement -------------------------------------------------------- */
 
 /* Time the batched copy kernel of whole-plan transfers (x == NULL) with HIP

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librdev.so")
-SOURCES = ["rdev.hip", "planner.cpp"]
+SOURCES = ["rdev.hip", "planner.cpp", "graph.cpp"]
 HEADERS = ["kernels.h", "planner.h"]
 
 

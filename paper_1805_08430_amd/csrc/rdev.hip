@@ -26,6 +26,14 @@ rdev_status fail(rdev_status st, std::string msg) {
     return st;
 }
 
+}  // namespace
+
+namespace rdev {
+rdev_status fail_msg(rdev_status st, const std::string &msg) { return fail(st, msg); }
+}  // namespace rdev
+
+namespace {
+
 #define HIP_TRY(expr)                                                                      \
     do {                                                                                   \
         hipError_t e_ = (expr);                                                            \

@@ -102,6 +102,15 @@ SYMBOLS = {
     "rdev_consume_reduce_max": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, _P, _P]),
     "rdev_recv_polling_async": (C.c_int32, [_P, _P, C.POINTER(C.c_uint32), C.c_uint32, _P, _P, _P, C.c_uint64,
                                             C.POINTER(C.c_uint64)]),
+    "rdev_graph_open": (C.c_int32, [C.POINTER(_P)]),
+    "rdev_graph_close": (C.c_int32, [_P]),
+    "rdev_graph_input": (C.c_int32, [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_int64), C.c_uint32, C.POINTER(C.c_uint32)]),
+    "rdev_graph_node": (C.c_int32, [_P, C.c_uint32, C.POINTER(C.c_uint32), C.c_uint32, C.POINTER(C.c_int64), C.c_uint32,
+                                    C.c_uint32, C.POINTER(C.c_uint32)]),
+    "rdev_graph_infer": (C.c_int32, [_P]),
+    "rdev_graph_value": (C.c_int32, [_P, C.c_uint32, C.POINTER(TensorDesc)]),
+    "rdev_graph_transfers": (C.c_int32, [_P, C.POINTER(C.c_uint32), C.c_uint32, C.POINTER(TensorDesc),
+                                         C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.c_uint32, C.POINTER(C.c_uint32)]),
     "rdev_tracer_open": (C.c_int32, [_P, _P, C.c_uint64, C.c_uint32, C.POINTER(_P)]),
     "rdev_tracer_close": (C.c_int32, [_P]),
     "rdev_tracer_begin_iteration": (C.c_int32, [_P]),
@@ -279,6 +288,58 @@ def rdev_recv_polling_async(dev: int, plan: int, tensor_ids: Sequence[int], out_
     st = _check(lib().rdev_recv_polling_async(dev, plan, arr, len(tensor_ids), out_ptr, flag_stream or None,
                                               consumer_stream or None, max_polls, C.byref(polls)))
     return st == OK, polls.value
+
+
+OP_UNARY, OP_BINARY, OP_MATMUL, OP_TRANSPOSE, OP_RESHAPE, OP_CONCAT, OP_REDUCE, OP_GATHER, OP_UNIQUE, OP_CONV2D, \
+    OP_GRAD, OP_CAST = range(12)
+
+
+def rdev_graph_open() -> int:
+    h = _P()
+    _check(lib().rdev_graph_open(C.byref(h)))
+    return h.value
+
+
+def rdev_graph_close(g: int) -> None:
+    _check(lib().rdev_graph_close(g))
+
+
+def rdev_graph_input(g: int, dtype: int, dims: Sequence[int], partition: int) -> int:
+    arr = (C.c_int64 * max(len(dims), 1))(*dims)
+    v = C.c_uint32()
+    _check(lib().rdev_graph_input(g, dtype, len(dims), arr, partition, C.byref(v)))
+    return v.value
+
+
+def rdev_graph_node(g: int, op: int, inputs: Sequence[int], attrs: Sequence[int], partition: int) -> int:
+    ins = (C.c_uint32 * max(len(inputs), 1))(*inputs)
+    at = (C.c_int64 * max(len(attrs), 1))(*attrs)
+    v = C.c_uint32()
+    _check(lib().rdev_graph_node(g, op, ins, len(inputs), at, len(attrs), partition, C.byref(v)))
+    return v.value
+
+
+def rdev_graph_infer(g: int) -> None:
+    _check(lib().rdev_graph_infer(g))
+
+
+def rdev_graph_value(g: int, value: int) -> TensorDesc:
+    d = TensorDesc()
+    _check(lib().rdev_graph_value(g, value, C.byref(d)))
+    return d
+
+
+def rdev_graph_transfers(g: int, partition_to_arena: Sequence[int]):
+    """Returns (descs, values, destination partitions)."""
+    p2a = (C.c_uint32 * max(len(partition_to_arena), 1))(*partition_to_arena)
+    n = C.c_uint32()
+    st = lib().rdev_graph_transfers(g, p2a, len(partition_to_arena), None, None, None, 0, C.byref(n))
+    if st not in (OK, E_NOMEM):
+        _check(st)
+    cap = max(n.value, 1)
+    descs, vals, parts = (TensorDesc * cap)(), (C.c_uint32 * cap)(), (C.c_uint32 * cap)()
+    _check(lib().rdev_graph_transfers(g, p2a, len(partition_to_arena), descs, vals, parts, cap, C.byref(n)))
+    return list(descs[:n.value]), list(vals[:n.value]), list(parts[:n.value])
 
 
 def rdev_tracer_open(dev: int, pool_base: int, pool_bytes: int, arena_id: int) -> int:
