@@ -234,6 +234,44 @@ def consumer_leg(R, torch, W, dev, wl, opts, s, spin, iters=20):
             "polling_async_us": round(med(t_async), 1), "gain": round(med(t_event) / med(t_async), 3)}
 
 
+def queues_leg(R, torch, W, dev, wl, opts, spin, iters=30):
+    """Section 3.1 lets the caller pick the queue pair a transfer uses.  The HIP
+    analogue is the stream: one explicit batch per destination arena, either all
+    on one stream or each on a stream of its own, against the single launch that
+    covers every arena."""
+    images = W.fill_sources(wl, 0)
+    ts = TransferSet(R, torch, W, dev, wl, images, opts)
+    del images
+    groups = {}
+    for i, t in enumerate(wl.tensors):
+        if t.is_static:
+            groups.setdefault(t.dst_arena, []).append(R.make_xfer(i))
+    groups = list(groups.values())
+    ids = [x.tensor_id for g in groups for x in g]
+    streams = [torch.cuda.Stream() for _ in groups]
+    res = {}
+    seq = 0
+    for name in ("one_launch", "per_arena_one_stream", "per_arena_own_stream"):
+        times = []
+        for it in range(iters + 3):
+            torch.cuda.synchronize()
+            seq += 1
+            t0 = time.perf_counter()
+            if name == "one_launch":
+                R.rdev_write_batch(dev, ts.plan, None, R.ZEROCOPY, seq, streams[0].cuda_stream)
+            else:
+                for k, g in enumerate(groups):
+                    st = streams[k if name == "per_arena_own_stream" else 0]
+                    R.rdev_write_batch(dev, ts.plan, g, R.ZEROCOPY, seq, st.cuda_stream)
+            spin(lambda: all(R.rdev_poll(dev, ts.plan, i) for i in ids))
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) * 1e6)
+            R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, streams[0].cuda_stream)
+        res[name] = round(sorted(times[3:])[len(times[3:]) // 2], 1)
+    ts.close()
+    return {"destination_arenas": len(groups), "us_per_iteration": res}
+
+
 def cpu_baseline(wl_name: str, seconds: float):
     """The CPU checker's static transfer on the same workload, as it stands."""
     import numpy as np
@@ -409,7 +447,8 @@ def main():
         msets = [TransferSet(R, torch, W, dev, wl, images, opts, copy_modes=True) for _ in range(2)]
         del images
         res = {}
-        for name, mode in (("zerocopy", R.ZEROCOPY), ("sendercopy", R.SENDERCOPY), ("rpc2", R.RPC2), ("rpc3", R.RPC3)):
+        for name, mode in (("zerocopy", R.ZEROCOPY), ("sendercopy", R.SENDERCOPY), ("rpc2", R.RPC2), ("rpc3", R.RPC3),
+                           ("runtime_memcpy_per_tensor", R.DMA)):
             run(5, msets, mode)
             torch.cuda.synchronize()
             m0 = time.perf_counter()
@@ -418,13 +457,15 @@ def main():
             res[name] = (time.perf_counter() - m0) / a.mode_steps * 1e6
         out["modes"] = {"us_per_iteration": {k: round(v, 2) for k, v in res.items()},
                         "slowdown_vs_zerocopy": {k: round(v / res["zerocopy"], 3) for k, v in res.items()},
-                        "algorithmic_hbm_bytes_per_payload_byte": {"zerocopy": 2, "sendercopy": 4, "rpc2": 4, "rpc3": 6},
+                        "algorithmic_hbm_bytes_per_payload_byte": {"zerocopy": 2, "sendercopy": 4, "rpc2": 4, "rpc3": 6,
+                                                                   "runtime_memcpy_per_tensor": 2},
                         "steps_each": a.mode_steps, "rotating_sets": 2}
         for ts in msets:
             ts.close()
         del msets
         out["tracing"] = tracing_leg(R, torch, dev, wl, s, spin)
         out["consumer_overlap"] = consumer_leg(R, torch, W, dev, wl, opts, s, spin)
+        out["queues"] = queues_leg(R, torch, W, dev, wl, opts, spin)
     if a.calibrate:
         nb = 256 << 20
         x = torch.ones(nb, dtype=torch.uint8, device="cuda:0")

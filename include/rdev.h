@@ -73,7 +73,8 @@ enum {
     RDEV_ZEROCOPY   = 0,  /* section 3.2: one-sided write into the pre-allocated region */
     RDEV_RPC2       = 1,  /* section 2.2: pack header+payload into a message buffer, unpack into a fresh allocation */
     RDEV_RPC3       = 2,  /* section 5.1 (RPC over RDMA): as RPC2 plus a buffer-to-buffer copy in between */
-    RDEV_SENDERCOPY = 3   /* section 5.1 (analysis off): stage into a registered buffer, then zero-copy write */
+    RDEV_SENDERCOPY = 3,  /* section 5.1 (analysis off): stage into a registered buffer, then zero-copy write */
+    RDEV_DMA        = 4   /* comparison only: one hipMemcpyAsync (device to device) per tensor instead of the batched kernel */
 };
 
 enum { RDEV_POLL_CONSUME = 1, RDEV_POLL_META = 2, RDEV_POLL_ARENA = 4 };
@@ -224,8 +225,8 @@ rdev_status rdev_plan_free(rdev_plan_t *plan);
  *                       For a dynamic tensor the metadata record is written
  *                       into the receiver's slot, then the metadata flag = seq;
  *                       the payload stays where it is until the receiver pulls.
- * mode != RDEV_ZEROCOPY applies to static tensors only and needs
- * rdev_plan_bind_buffers.  seq >= 1 is the value stored into the flags.
+ * mode != RDEV_ZEROCOPY takes the whole plan (x == NULL); the copying modes
+ * RDEV_RPC2 / RDEV_RPC3 / RDEV_SENDERCOPY need rdev_plan_bind_buffers.  seq >= 1 is the value stored into the flags.
  * The whole batch is validated before anything is enqueued. */
 rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
                              uint32_t mode, uint32_t seq, void *stream);

@@ -886,6 +886,26 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
     return RDEV_OK;
 }
 
+// comparison path: the runtime's own device-to-device copy, one call per tensor, then the flags
+static rdev_status write_dma_mode(rdev_plan_t *plan, uint32_t seq, hipStream_t s) {
+    if (!plan->bound_all) return fail(RDEV_E_STATE, "not every static tensor has a bound source");
+    RDEV_TRY(check_busy_all(plan));
+    std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
+    for (uint32_t i = 0; i < plan->pl.size(); ++i) {
+        const rdev_placement &p = plan->pl[i];
+        if (p.kind != RDEV_STATIC || !p.bytes) continue;
+        const SrcLoc &loc = plan->src[i];
+        HIP_TRY(hipMemcpyAsync(arena_ptr(plan, p.dst_arena, p.data_offset), plan->dev->arenas[loc.arena].base + loc.offset,
+                               p.bytes, hipMemcpyDeviceToDevice, s));
+    }
+    if (plan->n_static) {
+        hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
+                           plan->d_flags.ptr, plan->n_static, seq, plan->d_batch_view, next_token(plan, seq));
+        RDEV_TRY(launch_check("flag_table_kernel"));
+    }
+    return RDEV_OK;
+}
+
 // static tensors listed explicitly (write or pull: on one GPU the same movement)
 static rdev_status transfer_static_list(rdev_plan_t *plan, const std::vector<std::pair<uint32_t, const void *>> &list,
                                         uint32_t seq, hipStream_t s) {
@@ -907,11 +927,12 @@ rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_x
     if (!dev || !plan || plan->dev != dev) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
     if ((x == nullptr) != (n == 0)) return fail(RDEV_E_INVAL, "x and n must both be empty or both be given");
     if (!seq) return fail(RDEV_E_INVAL, "seq must be >= 1");
-    if (mode > RDEV_SENDERCOPY) return fail(RDEV_E_INVAL, "unknown mode");
+    if (mode > RDEV_DMA) return fail(RDEV_E_INVAL, "unknown mode");
     RDEV_TRY(require_gpu(dev));
     hipStream_t s = (hipStream_t)stream;
     if (mode != RDEV_ZEROCOPY) {
-        if (x) return fail(RDEV_E_INVAL, "copying modes take the whole plan (x == NULL)");
+        if (x) return fail(RDEV_E_INVAL, "modes other than RDEV_ZEROCOPY take the whole plan (x == NULL)");
+        if (mode == RDEV_DMA) return write_dma_mode(plan, seq, s);
         return write_copy_mode(plan, mode, seq, s);
     }
     if (!x) return write_static_all(plan, seq, s);

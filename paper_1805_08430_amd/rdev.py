@@ -27,7 +27,7 @@ _ERR_NAMES = {E_INVAL: "E_INVAL", E_NOMEM: "E_NOMEM", E_OVERLAP: "E_OVERLAP", E_
 U8, I8, I16, I32, I64, F16, BF16, F32, F64 = range(9)
 DTYPE = {"u8": U8, "i8": I8, "i16": I16, "i32": I32, "i64": I64, "f16": F16, "bf16": BF16, "f32": F32, "f64": F64}
 STATIC, DYNAMIC = 0, 1
-ZEROCOPY, RPC2, RPC3, SENDERCOPY = 0, 1, 2, 3
+ZEROCOPY, RPC2, RPC3, SENDERCOPY, DMA = 0, 1, 2, 3, 4
 POLL_CONSUME, POLL_META, POLL_ARENA = 1, 2, 4
 PLAN_CHECK_BUSY = 1
 

@@ -35,7 +35,7 @@ def _run_modes(wl, iters=2, **opts):
     static_ids = [i for i, t in enumerate(wl.tensors) if t.is_static]
     seq = 0
     for it in range(iters):
-        for gm, om in MODES + [(R.ZEROCOPY, None)]:
+        for gm, om in MODES + [(R.ZEROCOPY, None), (R.DMA, None)]:
             seq += 1
             if it or seq > 1:
                 imgs = W.fill_sources(wl, variant=seq)
@@ -101,5 +101,6 @@ def test_copy_mode_errors():
     assert status(R.rdev_write_batch, g.dev, g.plan, None, R.RPC2, 1, g.s) == R.E_NOMEM         # heap of 256 B
     assert status(R.rdev_write_batch, g.dev, g.plan, [R.make_xfer(0)], R.RPC2, 1, g.s) == R.E_INVAL
     assert status(R.rdev_write_batch, g.dev, g.plan, None, 7, 1, g.s) == R.E_INVAL
+    assert status(R.rdev_write_batch, g.dev, g.plan, [R.make_xfer(0)], R.DMA, 1, g.s) == R.E_INVAL
     _compare_all(g, o, "failed calls move nothing")
     g.close()
