@@ -54,7 +54,7 @@ def measured_traffic(workload):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "vgg16", "lstm", "inception"])
     ap.add_argument("--rotate", type=int, default=0,
