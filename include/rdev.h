@@ -259,6 +259,23 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
 rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
                       uint32_t poll_flags, rdev_meta *meta_out, void *stream);
 
+/* ---- sender-side producer of a run-time-sized tensor ----------------------- */
+
+/* The sparse case that motivates the dynamic path (section 3.3: shapes that
+ * depend on the mini-batch): from the token ids of a mini-batch, the ascending
+ * list of distinct ids and the rows of `table` they select.  Both outputs have a
+ * leading dim known only after the kernel ran; they are then sent with
+ * rdev_write_batch as dynamic tensors.
+ *   ids      device pointer, n_ids int64 values in [0, vocab)
+ *   table    device pointer, vocab rows of row_bytes each; 16-byte aligned, row_bytes % 16 == 0
+ *   out_ids  device pointer, room for min(n_ids, vocab) int64
+ *   out_rows device pointer, room for min(n_ids, vocab) * row_bytes, 16-byte aligned
+ *   count_out device pointer to two uint32: [0] = number of distinct ids, [1] = ids outside [0, vocab) (ignored)
+ * vocab <= 262144 (the id set is a bitmap in LDS).  Enqueued on `stream`. */
+rdev_status rdev_gather_unique_rows(rdev_device_t *dev, const int64_t *ids, uint32_t n_ids, uint32_t vocab,
+                                    const void *table, uint32_t row_bytes, int64_t *out_ids, void *out_rows,
+                                    uint32_t *count_out, void *stream);
+
 /* ---- receiver-side consumer (sections 4 and 5.1) -------------------------- */
 
 /* Result of the device-side consumer; lives in device memory. */

@@ -275,6 +275,68 @@ __global__ void rpc_flag_kernel(const FlagEnt *__restrict__ ents, uint8_t *const
     if (i == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+// ---- producer of the sparse case: distinct ids (ascending) and their rows ----
+
+constexpr uint32_t kUniqueThreads = 1024;
+constexpr uint32_t kUniqueMaxVocab = 262144;             // 32 KiB bitmap in LDS
+
+// One workgroup: mark every id in an LDS bitmap, rank the set bits with a
+// two-level prefix sum of population counts, write the ids out in ascending order.
+__global__ __launch_bounds__(kUniqueThreads) void unique_ids_kernel(const int64_t *__restrict__ ids, uint32_t n_ids,
+                                                                     uint32_t vocab, int64_t *__restrict__ out_ids,
+                                                                     uint32_t *__restrict__ count_out) {
+    __shared__ uint32_t bm[kUniqueMaxVocab / 32];
+    __shared__ uint32_t part[kUniqueThreads];
+    __shared__ uint32_t bad;
+    const uint32_t t = threadIdx.x;
+    const uint32_t words = (vocab + 31) / 32;
+    for (uint32_t w = t; w < words; w += kUniqueThreads) bm[w] = 0;
+    if (t == 0) bad = 0;
+    __syncthreads();
+    for (uint32_t i = t; i < n_ids; i += kUniqueThreads) {
+        const int64_t id = ids[i];
+        if (id >= 0 && id < (int64_t)vocab) atomicOr(&bm[(uint32_t)id >> 5], 1u << ((uint32_t)id & 31));
+        else atomicAdd(&bad, 1u);
+    }
+    __syncthreads();
+    const uint32_t seg = (words + kUniqueThreads - 1) / kUniqueThreads;      // contiguous words per lane
+    const uint32_t w0 = t * seg, w1 = min(w0 + seg, words);
+    uint32_t mine = 0;
+    for (uint32_t w = w0; w < w1; ++w) mine += __popc(bm[w]);
+    part[t] = mine;
+    __syncthreads();
+    for (uint32_t off = 1; off < kUniqueThreads; off <<= 1) {                // inclusive scan
+        const uint32_t v = t >= off ? part[t - off] : 0;
+        __syncthreads();
+        part[t] += v;
+        __syncthreads();
+    }
+    uint32_t rank = part[t] - mine;
+    for (uint32_t w = w0; w < w1; ++w) {
+        uint32_t bits = bm[w];
+        while (bits) {
+            const uint32_t b = __ffs(bits) - 1;
+            out_ids[rank++] = (int64_t)w * 32 + b;
+            bits &= bits - 1;
+        }
+    }
+    if (t == kUniqueThreads - 1) {
+        count_out[0] = part[t];
+        count_out[1] = bad;
+    }
+}
+
+// row r of the output <- table[out_ids[r]]; workgroups beyond the count leave at once
+__global__ __launch_bounds__(256) void gather_rows_kernel(const int64_t *__restrict__ out_ids,
+                                                           const uint32_t *__restrict__ count, const uint8_t *__restrict__ table,
+                                                           uint32_t row_bytes, uint8_t *__restrict__ out_rows) {
+    const uint32_t r = blockIdx.x;
+    if (r >= count[0]) return;
+    const v4u *s = (const v4u *)(table + (size_t)out_ids[r] * row_bytes);
+    v4u *d = (v4u *)(out_rows + (size_t)r * row_bytes);
+    for (uint32_t i = threadIdx.x; i < row_bytes / 16; i += 256) d[i] = __builtin_nontemporal_load(s + i);
+}
+
 // ---- receiver-side consumer (sections 4, 5.1) ----
 
 constexpr uint32_t kConsumeThreads = 256;

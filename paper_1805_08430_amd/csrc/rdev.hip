@@ -1161,6 +1161,27 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
     return RDEV_OK;
 }
 
+rdev_status rdev_gather_unique_rows(rdev_device_t *dev, const int64_t *ids, uint32_t n_ids, uint32_t vocab,
+                                    const void *table, uint32_t row_bytes, int64_t *out_ids, void *out_rows,
+                                    uint32_t *count_out, void *stream) {
+    if (!dev || (!ids && n_ids) || !table || !out_ids || !out_rows || !count_out) return fail(RDEV_E_INVAL, "NULL argument");
+    RDEV_TRY(require_gpu(dev));
+    if (!vocab || vocab > rdev::kUniqueMaxVocab) return fail(RDEV_E_INVAL, "vocab must be in 1 .. 262144");
+    if (!row_bytes || row_bytes % 16) return fail(RDEV_E_INVAL, "row_bytes must be a positive multiple of 16");
+    if (((uintptr_t)table | (uintptr_t)out_rows) & 15) return fail(RDEV_E_ALIGN, "table and out_rows must be 16-byte aligned");
+    if (((uintptr_t)ids | (uintptr_t)out_ids) & 7 || ((uintptr_t)count_out & 3)) return fail(RDEV_E_ALIGN, "ids, out_ids, count_out must be naturally aligned");
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(rdev::unique_ids_kernel, dim3(1), dim3(rdev::kUniqueThreads), 0, s, ids, n_ids, vocab, out_ids, count_out);
+    RDEV_TRY(launch_check("unique_ids_kernel"));
+    const uint32_t grid = std::min(n_ids, vocab);
+    if (grid) {
+        hipLaunchKernelGGL(rdev::gather_rows_kernel, dim3(grid), dim3(256), 0, s, out_ids, count_out, (const uint8_t *)table,
+                           row_bytes, (uint8_t *)out_rows);
+        RDEV_TRY(launch_check("gather_rows_kernel"));
+    }
+    return RDEV_OK;
+}
+
 // ---- receiver-side consumer (sections 4, 5.1) ----
 
 static rdev_status consume_checked(rdev_plan_t *plan, uint32_t idx, uint32_t max_spins, rdev_consume_result *out,

@@ -99,6 +99,7 @@ SYMBOLS = {
     "rdev_write_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, C.c_uint32, _P]),
     "rdev_read_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
     "rdev_poll": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, C.POINTER(Meta), _P]),
+    "rdev_gather_unique_rows": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P, _P, _P, _P]),
     "rdev_consume_reduce_max": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, _P, _P]),
     "rdev_recv_polling_async": (C.c_int32, [_P, _P, C.POINTER(C.c_uint32), C.c_uint32, _P, _P, _P, C.c_uint64,
                                             C.POINTER(C.c_uint64)]),
@@ -274,6 +275,12 @@ def rdev_poll(dev: int, plan: int, tensor_id: int = ALL_TENSORS, poll_flags: int
     if want_meta:
         return ready, (m if ready else None)
     return ready
+
+
+def rdev_gather_unique_rows(dev: int, ids_ptr: int, n_ids: int, vocab: int, table_ptr: int, row_bytes: int,
+                            out_ids_ptr: int, out_rows_ptr: int, count_ptr: int, stream: int = 0) -> None:
+    _check(lib().rdev_gather_unique_rows(dev, ids_ptr, n_ids, vocab, table_ptr, row_bytes, out_ids_ptr, out_rows_ptr,
+                                         count_ptr, stream or None))
 
 
 def rdev_consume_reduce_max(dev: int, plan: int, tensor_id: int, max_spins: int, out_ptr: int, stream: int = 0) -> None:
