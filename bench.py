@@ -31,7 +31,8 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for a plain 256 MiB device-to-device copy (profiles/copy_table_kernel_<workload>.md).
 # Valid only for the kernel sources they were taken with: `hash` covers csrc/kernels.h + csrc/rdev.hip.
 TRAFFIC = {
-    "vgg16": {"hash": "e221b6cb015abb59", "fetch_bytes": 557730222, "write_bytes": 553469356},
+    "vgg16": {"hash": "291181ed4509fc9b", "fetch_bytes": 557738360, "write_bytes": 553483472},
+    "inception": {"hash": "291181ed4509fc9b", "fetch_bytes": 969972847, "write_bytes": 962474826},
 }
 
 
