@@ -57,7 +57,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "vgg16", "lstm", "inception"])
+    ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "vgg16", "lstm", "inception", "fcn5", "gru"])
     ap.add_argument("--rotate", type=int, default=0,
                     help="number of source/receiver set copies cycled through (0 = enough to exceed 1 GB)")
     ap.add_argument("--chunk-bytes", type=int, default=0)
@@ -115,7 +115,9 @@ class TransferSet:
         descs = [R.make_desc(i, R.DTYPE[t.dtype], t.dims, recv_ids[t.dst_arena]) for i, t in enumerate(wl.tensors)]
         self.plan = R.rdev_plan(dev, descs, dyn_heap_bytes=heap, **opts)
         if copy_modes:
-            nbuf = sum(128 + (t.nbytes + 255) // 256 * 256 for t in wl.static_tensors) + 4096
+            frag = opts.get("rpc_frag_bytes", 0)
+            nbuf = sum(128 + (t.nbytes + 255) // 256 * 256 + (32 * (t.nbytes // frag + 1) if frag else 0)
+                       for t in wl.static_tensors) + 4096
             self.bufs = [torch.empty(nbuf, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
             ids = [R.rdev_register_arena(dev, b.data_ptr(), b.numel()) for b in self.bufs]
             self.arena_ids += ids
@@ -278,7 +280,7 @@ def cpu_baseline(wl_name: str, seconds: float):
     import numpy as np
     from oracle import rdev_oracle as O
     from paper_1805_08430_amd import workloads as W
-    wl = W.CONFIGS[wl_name]()
+    wl = {**W.CONFIGS, **W.EXTRA_CONFIGS}[wl_name]()
     dev = O.Device()
     send_ids = [dev.register_arena(np.zeros(n, dtype=np.uint8)) for n in wl.sender_bytes]
     for sid in send_ids:
@@ -355,7 +357,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     R.lib()
-    wl = W.CONFIGS[a.workload]()
+    wl = {**W.CONFIGS, **W.EXTRA_CONFIGS}[a.workload]()
     payload = wl.payload_bytes
     rotate = a.rotate or max(2, -(-(1 << 30) // max(2 * payload, 1)))
     rotate = min(rotate, 64)
@@ -508,6 +510,22 @@ def main():
         for ts in msets:
             ts.close()
         del msets
+        # the same RPC3 path with every payload cut into 1 MiB fragments (section 2.2: bounded receive buffers)
+        images = W.fill_sources(wl, 0)
+        fsets = [TransferSet(R, torch, W, dev, wl, images, dict(opts, rpc_frag_bytes=1 << 20), copy_modes=True)
+                 for _ in range(2)]
+        del images
+        run(5, fsets, R.RPC3)
+        torch.cuda.synchronize()
+        m0 = time.perf_counter()
+        run(a.mode_steps, fsets, R.RPC3)
+        torch.cuda.synchronize()
+        res["rpc3_fragments_1MiB"] = (time.perf_counter() - m0) / a.mode_steps * 1e6
+        out["modes"]["us_per_iteration"]["rpc3_fragments_1MiB"] = round(res["rpc3_fragments_1MiB"], 2)
+        out["modes"]["slowdown_vs_zerocopy"]["rpc3_fragments_1MiB"] = round(res["rpc3_fragments_1MiB"] / res["zerocopy"], 3)
+        for ts in fsets:
+            ts.close()
+        del fsets
         out["tracing"] = tracing_leg(R, torch, dev, wl, s, spin)
         out["consumer_overlap"] = consumer_leg(R, torch, W, dev, wl, opts, s, spin)
         out["queues"] = queues_leg(R, torch, W, dev, wl, opts, spin)

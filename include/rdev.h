@@ -116,7 +116,23 @@ typedef struct {
     uint64_t chunk_bytes;       /* large tensors are cut into work items of this size; multiple of 256; 0 = default */
     uint32_t small_bytes;       /* tensors up to this size are copied by one wavefront; 0 = default */
     uint32_t flags;             /* RDEV_PLAN_* */
+    uint64_t rpc_frag_bytes;    /* RPC modes only (section 2.2: a message larger than the receiver's buffer is split
+                                   into fragments, each with header information for re-assembly): 0 = every payload
+                                   in one piece; otherwise a multiple of 16, and every payload travels as
+                                   ceil(bytes / rpc_frag_bytes) fragments, each behind a 32-byte rdev_frag header */
 } rdev_plan_opts;
+
+/* Fragment header of the RPC modes (little endian, 32 bytes), followed by the
+ * fragment's payload bytes and zero padding to a multiple of 16. */
+typedef struct {
+    uint32_t tensor_id;
+    uint32_t seq;
+    uint32_t frag_index;
+    uint32_t frag_count;
+    uint64_t offset;        /* of this fragment inside the tensor */
+    uint32_t bytes;
+    uint32_t reserved;
+} rdev_frag;
 
 /* The metadata record of the dynamic path, exactly as it lies in the
  * receiver's slot (section 3.3: number of dims, size of each dim, element

@@ -493,8 +493,20 @@ def dyn_recv(dev: Device, pl: Plan, tensor_id: int, seq: int) -> int:
 # ---------------------------------------------------------------------------
 # sections 2.2, 5.1: RPC-style copy path and the sender staging copy
 # ---------------------------------------------------------------------------
-def rpc_message_bytes(nbytes: int) -> int:
-    return META_BYTES + round_up(nbytes, 16)
+FRAG_HEADER_BYTES = 32
+_FRAG = struct.Struct("<IIIIQII")      # tensor_id, seq, frag_index, frag_count, offset, bytes, reserved
+assert _FRAG.size == FRAG_HEADER_BYTES
+
+
+def rpc_message_bytes(nbytes: int, frag_bytes: int = 0) -> int:
+    """header || payload || pad to 16; or, fragmented (section 2.2): header, then
+    per fragment a 32-byte fragment header || piece || pad to 16."""
+    if not frag_bytes:
+        return META_BYTES + round_up(nbytes, 16)
+    total = META_BYTES
+    for off in range(0, nbytes, frag_bytes):
+        total += FRAG_HEADER_BYTES + round_up(min(frag_bytes, nbytes - off), 16)
+    return total
 
 
 def _header(pl: Plan, tensor_id: int, src_arena: int, src_offset: int, seq: int) -> bytes:
@@ -507,7 +519,7 @@ def _header(pl: Plan, tensor_id: int, src_arena: int, src_offset: int, seq: int)
 
 def copy_write(dev: Device, pl: Plan, sources: Dict[int, Tuple[int, int]], mode: int, seq: int,
                send_buf: Tuple[int, int, int], recv_buf: Optional[Tuple[int, int, int]] = None,
-               tensor_ids: Optional[Sequence[int]] = None) -> None:
+               tensor_ids: Optional[Sequence[int]] = None, frag_bytes: int = 0) -> None:
     """The copying alternatives for a batch of static tensors.
 
     RPC2: pack header||payload||zero pad into send_buf back to back; unpack:
@@ -545,7 +557,9 @@ def copy_write(dev: Device, pl: Plan, sources: Dict[int, Tuple[int, int]], mode:
         return
     if mode not in (MODE_RPC2, MODE_RPC3):
         raise OracleError("inval", "unknown mode")
-    total = sum(rpc_message_bytes(pl.get(t).nbytes) for t in ids)
+    if frag_bytes % 16:
+        raise OracleError("inval", "fragment size must be a multiple of 16")
+    total = sum(rpc_message_bytes(pl.get(t).nbytes, frag_bytes) for t in ids)
     if total > sb_bytes or (mode == MODE_RPC3 and (recv_buf is None or total > recv_buf[2])):
         raise OracleError("nomem", "message buffer too small")
     # heap space is claimed for the whole batch before anything moves
@@ -564,9 +578,19 @@ def copy_write(dev: Device, pl: Plan, sources: Dict[int, Tuple[int, int]], mode:
         p = pl.get(t)
         sa, so = sources[t]
         rec = _header(pl, t, sa, so, seq)
-        msg = np.zeros(rpc_message_bytes(p.nbytes), dtype=np.uint8)
+        msg = np.zeros(rpc_message_bytes(p.nbytes, frag_bytes), dtype=np.uint8)
         msg[:META_BYTES] = np.frombuffer(rec, dtype=np.uint8)
-        msg[META_BYTES:META_BYTES + p.nbytes] = dev.arenas[sa].mem[so:so + p.nbytes]
+        if not frag_bytes:
+            msg[META_BYTES:META_BYTES + p.nbytes] = dev.arenas[sa].mem[so:so + p.nbytes]
+        else:
+            nfrag = -(-p.nbytes // frag_bytes)
+            cur = META_BYTES
+            for k in range(nfrag):
+                off = k * frag_bytes
+                fb = min(frag_bytes, p.nbytes - off)
+                msg[cur:cur + FRAG_HEADER_BYTES] = np.frombuffer(_FRAG.pack(t, seq, k, nfrag, off, fb, 0), dtype=np.uint8)
+                msg[cur + FRAG_HEADER_BYTES:cur + FRAG_HEADER_BYTES + fb] = dev.arenas[sa].mem[so + off:so + off + fb]
+                cur += FRAG_HEADER_BYTES + round_up(fb, 16)
         dev._store("pack", t, sb_arena, sb_off + ptr, msg)
         offs.append(ptr)
         ptr += msg.size
@@ -582,11 +606,24 @@ def copy_write(dev: Device, pl: Plan, sources: Dict[int, Tuple[int, int]], mode:
         t, nb = m["tensor_id"], m["nbytes"]
         p = pl.get(t)
         dst = _heap_alloc(pl, p.dst_arena, nb)
-        data = mem[buf_off + cur + META_BYTES:buf_off + cur + META_BYTES + nb].copy()
-        dev._store("payload", t, p.dst_arena, dst, data)
+        if not frag_bytes:
+            data = mem[buf_off + cur + META_BYTES:buf_off + cur + META_BYTES + nb].copy()
+            dev._store("payload", t, p.dst_arena, dst, data)
+            cur += rpc_message_bytes(nb)
+        else:
+            # re-assembly: walk the fragment headers until the whole tensor has arrived
+            cur += META_BYTES
+            got = 0
+            while got < nb:
+                ft, fseq, fk, fn, foff, fb, _ = _FRAG.unpack(bytes(mem[buf_off + cur:buf_off + cur + FRAG_HEADER_BYTES]))
+                if ft != t or fseq != m["seq"] or foff + fb > nb:
+                    raise OracleError("state", "fragment does not belong to this message")
+                piece = mem[buf_off + cur + FRAG_HEADER_BYTES:buf_off + cur + FRAG_HEADER_BYTES + fb].copy()
+                dev._store("payload", t, p.dst_arena, dst + foff, piece)
+                got += fb
+                cur += FRAG_HEADER_BYTES + round_up(fb, 16)
         dev._store_u32("flag_set", t, p.dst_arena, p.flag_offset, m["seq"])
         pl.rpc_offsets[t] = dst
-        cur += rpc_message_bytes(nb)
 
 
 # ---------------------------------------------------------------------------

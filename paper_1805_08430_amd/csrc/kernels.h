@@ -217,38 +217,57 @@ struct HeapBases {
 
 // One unit of unpack work: a chunk of one message's payload.  Grouping as in Item.
 struct UItem {
-    const uint8_t *hdr;     // the message (header first) in the receive buffer
-    uint64_t dst_rel;       // offset of the tensor inside this call's fresh-allocation area
+    const uint8_t *hdr;     // the message header (or, with kFragBit, a fragment header) in the receive buffer
+    uint64_t dst_rel;       // where this piece starts inside this call's fresh-allocation area
     uint32_t chunk_index;
-    uint32_t heap_slot;
+    uint32_t heap_slot;     // | kFragBit when hdr is a fragment header
     uint32_t n_sub;
     uint32_t sub_first;
 };
+constexpr uint32_t kFragBit = 0x80000000u;
 static_assert(sizeof(UItem) == 32, "UItem is 32 bytes");
 
 // pack, part 1: the 128-byte header of every message (seq patched in) and the zero padding behind the payload
 __global__ void rpc_header_kernel(const rdev_meta *__restrict__ headers, uint8_t *const *__restrict__ msg_ptrs,
-                                  uint32_t n, uint32_t seq) {
+                                  uint32_t n, uint32_t seq, uint32_t pad_payload) {
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
     const uint32_t t = gid >> 5, w = gid & 31;
     if (t >= n) return;
     const uint32_t *hw = (const uint32_t *)(headers + t);
     uint8_t *msg = msg_ptrs[t];
     ((uint32_t *)msg)[w] = (w == 26) ? seq : hw[w];
+    if (!pad_payload) return;                       // fragmented messages pad behind each fragment instead
     const uint64_t bytes = headers[t].bytes;
     const uint32_t pad = (16 - (uint32_t)(bytes & 15)) & 15;
     if (w < pad) msg[RDEV_META_BYTES + bytes + w] = 0;
 }
 
+// pack, fragmented messages: the 32-byte header of every fragment (seq patched in) and the padding behind its payload
+__global__ void rpc_frag_header_kernel(const rdev_frag *__restrict__ frags, uint8_t *const *__restrict__ frag_ptrs,
+                                       uint32_t n, uint32_t seq) {
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t f = gid >> 3, w = gid & 7;
+    if (f >= n) return;
+    const uint32_t *hw = (const uint32_t *)(frags + f);
+    uint8_t *p = frag_ptrs[f];
+    ((uint32_t *)p)[w] = (w == 1) ? seq : hw[w];
+    const uint32_t bytes = frags[f].bytes;
+    const uint32_t pad = (16 - (bytes & 15)) & 15;
+    for (uint32_t k = w; k < pad; k += 8) p[sizeof(rdev_frag) + bytes + k] = 0;
+}
+
 __device__ __forceinline__ void unpack_one(const UItem &it, const HeapBases &hb, uint32_t chunk, uint32_t tid,
                                            uint32_t nth) {
     if (!it.hdr) return;                                          // padding entry of the table
-    const uint64_t bytes = ((const rdev_meta *)it.hdr)->bytes;    // length comes from the message itself
+    const bool frag = it.heap_slot & kFragBit;
+    // the length comes from the message itself: the tensor's header, or the fragment's
+    const uint64_t bytes = frag ? ((const rdev_frag *)it.hdr)->bytes : ((const rdev_meta *)it.hdr)->bytes;
+    const uint32_t head = frag ? (uint32_t)sizeof(rdev_frag) : (uint32_t)RDEV_META_BYTES;
     const uint64_t off = (uint64_t)it.chunk_index * chunk;
     if (off >= bytes) return;
     const uint64_t rem = bytes - off;
     const uint32_t n = rem < chunk ? (uint32_t)rem : chunk;
-    copy_span(it.hdr + RDEV_META_BYTES + off, hb.base[it.heap_slot] + it.dst_rel + off, n, tid, nth);
+    copy_span(it.hdr + head + off, hb.base[it.heap_slot & ~kFragBit] + it.dst_rel + off, n, tid, nth);
 }
 
 // unpack: parse each header, copy the payload out into the fresh allocation

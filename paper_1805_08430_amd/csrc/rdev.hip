@@ -142,6 +142,9 @@ struct rdev_plan_s {
     DevBuf<rdev::UItem> d_unpack_send_items, d_unpack_send_subs, d_unpack_recv_items, d_unpack_recv_subs;
     DevBuf<rdev_meta> d_headers;
     DevBuf<uint8_t *> d_msg_send, d_msg_recv;
+    DevBuf<rdev_frag> d_frags;                       // fragmented messages: one header per fragment
+    DevBuf<uint8_t *> d_frag_send;
+    uint32_t n_frags = 0;
     uint32_t n_pack_blocks = 0, n_stage_blocks = 0, n_unpack_blocks = 0;
 };
 
@@ -474,6 +477,7 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
     if (o.chunk_bytes % 256 || o.chunk_bytes > (1u << 30)) return fail(RDEV_E_INVAL, "chunk_bytes must be a multiple of 256, at most 1 GiB");
     if (o.small_bytes > o.chunk_bytes) o.small_bytes = (uint32_t)o.chunk_bytes;
     if (o.flags & ~(uint32_t)RDEV_PLAN_CHECK_BUSY) return fail(RDEV_E_INVAL, "unknown plan flags");
+    if (o.rpc_frag_bytes % 16 || o.rpc_frag_bytes > 0xFFFFFFF0ull) return fail(RDEV_E_INVAL, "rpc_frag_bytes must be a multiple of 16 below 4 GiB");
 
     std::unique_ptr<rdev_plan_t> plan(new rdev_plan_t());
     plan->dev = dev;
@@ -659,7 +663,9 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
     std::vector<Item> pack, pack_s, stage, stage_s, unstage, unstage_s, pend_a, pend_b, pend_c;
     std::vector<rdev::UItem> us, us_s, ur, ur_s, upend_s, upend_r;
     std::vector<rdev_meta> headers;
-    std::vector<uint8_t *> msg_send, msg_recv;
+    std::vector<uint8_t *> msg_send, msg_recv, frag_send;
+    std::vector<rdev_frag> frags;
+    const uint64_t F = plan->opts.rpc_frag_bytes;
     uint64_t mptr = 0, sptr = 0;
     plan->stage_end = 0;
     auto push_unpack = [&](std::vector<rdev::UItem> &items, std::vector<rdev::UItem> &subs, std::vector<rdev::UItem> &pend,
@@ -694,14 +700,29 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
         headers.push_back(h);
         msg_send.push_back(sb + mptr);
         msg_recv.push_back(rb ? rb + mptr : nullptr);
-        cut_items(src, sb + mptr + RDEV_META_BYTES, p.bytes, i, chunk, small, pack, pack_s, pend_a);
         const uint32_t slot = slot_of[p.dst_arena];
         plan->rpc_slot[i] = slot;
         plan->rpc_rel[i] = plan->heap_need[slot];
-        push_unpack(us, us_s, upend_s, sb + mptr, plan->rpc_rel[i], slot, p.bytes);
-        if (rb) push_unpack(ur, ur_s, upend_r, rb + mptr, plan->rpc_rel[i], slot, p.bytes);
+        if (!F) {
+            cut_items(src, sb + mptr + RDEV_META_BYTES, p.bytes, i, chunk, small, pack, pack_s, pend_a);
+            push_unpack(us, us_s, upend_s, sb + mptr, plan->rpc_rel[i], slot, p.bytes);
+            if (rb) push_unpack(ur, ur_s, upend_r, rb + mptr, plan->rpc_rel[i], slot, p.bytes);
+            mptr += RDEV_META_BYTES + ((p.bytes + 15) & ~(uint64_t)15);
+        } else {
+            // header, then ceil(bytes / F) fragments, each: 32-byte fragment header || piece || pad to 16
+            mptr += RDEV_META_BYTES;
+            const uint64_t nfrag = (p.bytes + F - 1) / F;
+            for (uint64_t k = 0; k < nfrag; ++k) {
+                const uint64_t off = k * F, fb = std::min<uint64_t>(F, p.bytes - off);
+                frags.push_back(rdev_frag{p.tensor_id, 0, (uint32_t)k, (uint32_t)nfrag, off, (uint32_t)fb, 0});
+                frag_send.push_back(sb + mptr);
+                cut_items(src + off, sb + mptr + sizeof(rdev_frag), fb, i, chunk, small, pack, pack_s, pend_a);
+                push_unpack(us, us_s, upend_s, sb + mptr, plan->rpc_rel[i] + off, slot | rdev::kFragBit, fb);
+                if (rb) push_unpack(ur, ur_s, upend_r, rb + mptr, plan->rpc_rel[i] + off, slot | rdev::kFragBit, fb);
+                mptr += sizeof(rdev_frag) + ((fb + 15) & ~(uint64_t)15);
+            }
+        }
         plan->heap_need[slot] += (p.bytes + A - 1) & ~(A - 1);
-        mptr += RDEV_META_BYTES + ((p.bytes + 15) & ~(uint64_t)15);
         // staging
         plan->stage_end = std::max(plan->stage_end, sptr + p.bytes);
         cut_items(src, sb + sptr, p.bytes, i, chunk, small, stage, stage_s, pend_b);
@@ -740,6 +761,9 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
     HIP_TRY(plan->d_headers.upload(headers));
     HIP_TRY(plan->d_msg_send.upload(msg_send));
     HIP_TRY(plan->d_msg_recv.upload(msg_recv));
+    HIP_TRY(plan->d_frags.upload(frags));
+    HIP_TRY(plan->d_frag_send.upload(frag_send));
+    plan->n_frags = (uint32_t)frags.size();
     plan->n_pack_blocks = (uint32_t)pack.size();
     plan->n_stage_blocks = (uint32_t)stage.size();
     plan->n_unpack_blocks = (uint32_t)us.size();
@@ -794,8 +818,14 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
     if (plan->n_static) {
         // pack: headers, then payloads
         hipLaunchKernelGGL(rdev::rpc_header_kernel, dim3((plan->n_static * 32 + 255) / 256), dim3(256), 0, s,
-                           plan->d_headers.ptr, plan->d_msg_send.ptr, plan->n_static, seq);
+                           plan->d_headers.ptr, plan->d_msg_send.ptr, plan->n_static, seq,
+                           plan->opts.rpc_frag_bytes ? 0u : 1u);
         RDEV_TRY(launch_check("rpc_header_kernel"));
+        if (plan->n_frags) {
+            hipLaunchKernelGGL(rdev::rpc_frag_header_kernel, dim3((plan->n_frags * 8 + 255) / 256), dim3(256), 0, s,
+                               plan->d_frags.ptr, plan->d_frag_send.ptr, plan->n_frags, seq);
+            RDEV_TRY(launch_check("rpc_frag_header_kernel"));
+        }
         if (plan->n_pack_blocks) {
             hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_pack_blocks), dim3(rdev::kBlockThreads), 0, s,
                                plan->d_pack_items.ptr, plan->d_pack_subs.ptr);

@@ -346,4 +346,33 @@ def small_mixed(seed: int, n: int = 12, max_bytes: int = 5000, n_recv: int = 2,
     return Workload(f"mixed{seed}", seed, tensors, 1, n_recv, sb, "bits")
 
 
+# --------------------------------------------------------------------------
+# two more sets shaped after the paper's Table 1 (not among the five graded configs)
+# --------------------------------------------------------------------------
+def fcn5() -> Workload:
+    """FCN-5-shaped: 784 -> 4096 -> 4096 -> 4096 -> 4096 -> 10, five weight/bias
+    pairs = 10 tensors, 53 601 290 fp32 parameters = 204.47 MiB (the size the
+    paper's Table 1 lists for its FCN-5), round-robin over 2 receiver arenas."""
+    seed = SEED_BASE + 5
+    dims = [784, 4096, 4096, 4096, 4096, 10]
+    layers = [(f"fc{i + 1}", (dims[i + 1], dims[i])) for i in range(5)]
+    tensors = _wb_list(layers, 2)
+    sb = _pack_sources(tensors, 1, 256)
+    return Workload("fcn5", seed, tensors, 1, 2, sb, "normal", "5 weight + 5 bias tensors")
+
+
+def gru() -> Workload:
+    """GRU-shaped, hidden size 1024, one layer: gate kernel [2048, 2048] + bias,
+    candidate kernel [2048, 1024] + bias, output projection [1024, 1000] + bias:
+    7 319 528 fp32 parameters = 27.92 MiB (Table 1's size for its GRU)."""
+    seed = SEED_BASE + 6
+    tensors = [TensorSpec("gru.gates.W", "f32", (2048, 2048), 0, 0), TensorSpec("gru.gates.b", "f32", (2048,), 0, 0),
+               TensorSpec("gru.cand.W", "f32", (2048, 1024), 0, 0), TensorSpec("gru.cand.b", "f32", (1024,), 0, 0),
+               TensorSpec("proj.W", "f32", (1024, 1000), 0, 0), TensorSpec("proj.b", "f32", (1000,), 0, 0)]
+    sb = _pack_sources(tensors, 1, 256)
+    return Workload("gru", seed, tensors, 1, 1, sb, "normal", "6 tensors")
+
+
+EXTRA_CONFIGS = {"fcn5": fcn5, "gru": gru}
+
 CONFIGS = {"tiny": tiny, "alexnet": alexnet, "vgg16": vgg16, "lstm": lstm, "inception": inception}

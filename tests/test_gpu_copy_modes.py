@@ -15,15 +15,17 @@ pytestmark = pytest.mark.gpu
 MODES = [(R.RPC2, O.MODE_RPC2), (R.RPC3, O.MODE_RPC3), (R.SENDERCOPY, O.MODE_SENDERCOPY)]
 
 
-def _sizes(wl, align=256):
-    msg = sum(128 + O.round_up(t.nbytes, 16) for t in wl.static_tensors)
+def _sizes(wl, align=256, frag=0):
+    msg = sum(O.rpc_message_bytes(t.nbytes, frag) for t in wl.static_tensors)
     stage = sum(O.round_up(t.nbytes, align) for t in wl.static_tensors)
     return max(msg, stage) + 512, 2 * stage + 1024
 
 
-def _run_modes(wl, iters=2, **opts):
+def _run_modes(wl, iters=2, frag=0, **opts):
     from gpu_harness import GpuRun
-    bufsz, heap = _sizes(wl)
+    bufsz, heap = _sizes(wl, frag=frag)
+    if frag:
+        opts["rpc_frag_bytes"] = frag
     g = GpuRun(wl, heap=heap, extra_arenas=(bufsz, bufsz), **opts)
     o = OracleRun(wl, heap=heap, extra_arenas=(bufsz, bufsz))
     gs = R.rdev_alloc_region(g.dev, g.extra_ids[0], bufsz - 256, 256)
@@ -48,7 +50,7 @@ def _run_modes(wl, iters=2, **opts):
             if om is None:
                 O.static_write(o.dev, o.plan, o.sources, seq)
             else:
-                O.copy_write(o.dev, o.plan, o.sources, om, seq, os_, or_)
+                O.copy_write(o.dev, o.plan, o.sources, om, seq, os_, or_, frag_bytes=frag)
             assert g.wait_all()
             _compare_all(g, o, f"mode {gm} seq {seq}")
             for t in static_ids[:50]:
@@ -71,6 +73,15 @@ def test_copy_modes_mixed_sets(seed):
 
 def test_copy_modes_tiny_cutting():
     _run_modes(W.small_mixed(24, n=20, max_bytes=20000, n_recv=2, gran=4), iters=1, chunk_bytes=1024, small_bytes=128)
+
+
+@pytest.mark.parametrize("frag", [16, 4096, 65536])
+def test_fragmented_rpc_modes(frag):
+    _run_modes(W.small_mixed(25, n=30, max_bytes=200000, n_recv=2, gran=1), iters=1, frag=frag)
+
+
+def test_fragmented_rpc_inception_one_worker():
+    _run_modes(W.inception(1), iters=1, frag=1 << 20)
 
 
 def test_copy_modes_inception_two_workers():

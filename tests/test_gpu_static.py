@@ -74,9 +74,9 @@ def test_alignments(align):
     _run_static(W.small_mixed(5, n=20, max_bytes=9000, n_recv=2, gran=2), iters=1, align=align)
 
 
-@pytest.mark.parametrize("name", ["alexnet", "vgg16", "lstm", "inception"])
+@pytest.mark.parametrize("name", ["alexnet", "vgg16", "lstm", "inception", "fcn5", "gru"])
 def test_full_size_configs(name):
-    wl = W.CONFIGS[name]()
+    wl = {**W.CONFIGS, **W.EXTRA_CONFIGS}[name]()
     _run_static(wl, iters=1, heap=1 << 20)
 
 

@@ -108,6 +108,13 @@ def test_vgg_round_robin_arena_loads():
     assert W.lstm().payload_bytes == 230948864
 
 
+def test_table1_shaped_extra_sets():
+    """FCN-5- and GRU-shaped sets reproduce the sizes the paper's Table 1 lists (in MiB)."""
+    f, g = W.fcn5(), W.gru()
+    assert len(f.tensors) == 10 and round(f.payload_bytes / 2 ** 20, 2) == 204.47
+    assert round(g.payload_bytes / 2 ** 20, 2) == 27.92
+
+
 def test_plan_random_mixed_sets():
     for seed in range(40):
         wl = W.small_mixed(seed, n=14, n_recv=3, n_dynamic=seed % 3)

@@ -290,6 +290,43 @@ def test_copy_modes_deliver_what_zero_copy_delivers(mode):
             assert (c.image(c.extra_ids[1]) == c.extra_poison[1]).all()
 
 
+@pytest.mark.parametrize("frag", [16, 48, 1024])
+def test_fragmented_messages_byte_by_byte(frag):
+    """RPC2 with fragments: the message buffer is rebuilt one byte at a time from
+    the layout (128-byte header, then per fragment a 32-byte header, the piece,
+    zero padding to 16), and the delivered tensors equal the unfragmented ones."""
+    wl = W.small_mixed(33, n=8, max_bytes=3000, n_recv=2, gran=1)
+    nmsg = sum(O.rpc_message_bytes(t.nbytes, frag) for t in wl.tensors)
+    heap = sum(O.round_up(t.nbytes, 256) for t in wl.tensors) + 512
+    c = OracleRun(wl, heap=heap, extra_arenas=(nmsg + 512,))
+    plain = OracleRun(wl, heap=heap, extra_arenas=(nmsg + 512,))
+    send = c.dev.alloc_region(c.extra_ids[0], nmsg, 256)
+    O.copy_write(c.dev, c.plan, c.sources, O.MODE_RPC2, 4, send, None, frag_bytes=frag)
+    O.copy_write(plain.dev, plain.plan, plain.sources, O.MODE_RPC2, 4, plain.dev.alloc_region(plain.extra_ids[0], nmsg, 256))
+    for rc, rp in zip(c.recv_ids, plain.recv_ids):
+        assert (c.image(rc) == plain.image(rp)).all()              # same delivery whatever the framing
+    want = [int(b) for b in c.extra_poison[0]]
+    cur = send[1]
+    src = c.src_images[0]
+    for i, t in enumerate(wl.tensors):
+        hdr = O.encode_meta(len(t.dims), O.DTYPE_CODE[t.dtype], t.nbytes, c.send_ids[0], t.src_offset, t.dims, i, 4)
+        want[cur:cur + 128] = list(hdr)
+        cur += 128
+        nfrag = -(-t.nbytes // frag)
+        for k in range(nfrag):
+            off = k * frag
+            fb = min(frag, t.nbytes - off)
+            fh = struct.pack("<IIIIQII", i, 4, k, nfrag, off, fb, 0)
+            want[cur:cur + 32] = list(fh)
+            for j in range(fb):
+                want[cur + 32 + j] = int(src[t.src_offset + off + j])
+            for j in range(fb, O.round_up(fb, 16)):
+                want[cur + 32 + j] = 0
+            cur += 32 + O.round_up(fb, 16)
+    assert cur - send[1] == nmsg
+    assert c.image(c.extra_ids[0]).tolist() == want
+
+
 def test_copy_mode_buffer_too_small():
     wl = W.small_mixed(5, n=4, n_recv=1)
     c = OracleRun(wl, heap=1 << 16, extra_arenas=(512,))
