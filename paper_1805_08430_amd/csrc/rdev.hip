@@ -976,6 +976,10 @@ rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_x
         RDEV_TRY(index_of(plan, x[k].tensor_id, &idx));
         const rdev_placement &p = plan->pl[idx];
         if (p.kind == RDEV_STATIC) {
+            ResolvedStatic r;
+            RDEV_TRY(resolve_static(plan, idx, x[k].src, &r));
+            if ((plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && static_ready(plan, idx))
+                return fail(RDEV_E_BUSY, "tensor " + std::to_string(p.tensor_id) + " has not been consumed");
             statics.emplace_back(idx, x[k].src);
             continue;
         }
@@ -1059,6 +1063,8 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
         if (p.kind == RDEV_STATIC) {
             ResolvedStatic r;
             RDEV_TRY(resolve_static(plan, idx, x[k].src, &r));
+            if ((plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && static_ready(plan, idx))
+                return fail(RDEV_E_BUSY, "tensor " + std::to_string(p.tensor_id) + " has not been consumed");
             continue;
         }
         const int32_t di = plan->dyn_index[idx];

@@ -134,6 +134,13 @@ def test_dynamic_errors_and_heap_exhaustion():
     assert status(wb, [R.make_xfer(d0, None, R.F32, (3, 8))]) == R.E_INVAL         # no source
     assert status(wb, [R.make_xfer(d0, 0x10, R.F32, (3, 8))]) == R.E_RANGE         # unregistered memory
     assert status(wb, [R.make_xfer(d0, src, R.F32, (1 << 20, 8))]) == R.E_RANGE    # longer than the arena
+    # a mixed batch whose LAST entry is bad moves nothing at all, not even its good first entries
+    big = max(range(4), key=lambda i: wl.tensors[i].nbytes)
+    inside = g.recv_t[0].data_ptr() + R.rdev_plan_get(g.plan, big).data_offset
+    assert status(wb, [R.make_xfer(d0, src, R.F32, (3, 8)), R.make_xfer(0), R.make_xfer(big, inside)]) == R.E_OVERLAP
+    assert status(wb, [R.make_xfer(0), R.make_xfer(d0, src, R.F32, (3, 8)), R.make_xfer(77)]) == R.E_INVAL
+    g.stream.synchronize()
+    assert not R.rdev_poll(g.dev, g.plan, d0, R.POLL_META) and not R.rdev_poll(g.dev, g.plan, 0)
     _compare_all(g, o, "nothing written by failed calls")
     # two tensors, the heap (2048 B) takes only the first
     wb([R.make_xfer(d0, src, R.F32, (40, 8)), R.make_xfer(d1, src + 4096, R.F32, (40, 8))])
