@@ -62,6 +62,8 @@ def parse():
                     help="number of source/receiver set copies cycled through (0 = enough to exceed 1 GB)")
     ap.add_argument("--chunk-bytes", type=int, default=0)
     ap.add_argument("--small-bytes", type=int, default=0)
+    ap.add_argument("--flag-groups", type=int, default=0,
+                    help="launches per whole-plan transfer, each followed by its tensors' flags (default one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-modes", action="store_true", help="skip the untimed comparison with the copying modes")
     ap.add_argument("--mode-steps", type=int, default=60)
@@ -232,9 +234,29 @@ def consumer_leg(R, torch, W, dev, wl, opts, s, spin, iters=20):
             torch.cuda.synchronize()
             (t_event if variant == "event" else t_async).append((time.perf_counter() - t0) * 1e6)
     ts.close()
+    # the batched transfer cut into groups that publish their flags one after the other, received polling-async
+    grouped = {}
+    for G in (1, 4, 8):
+        images = W.fill_sources(wl, 0)
+        tg = TransferSet(R, torch, W, dev, wl, images, dict(opts, flag_groups=G))
+        del images
+        tt = []
+        for it in range(iters + 2):
+            torch.cuda.synchronize()
+            seq += 1
+            t0 = time.perf_counter()
+            R.rdev_write_batch(dev, tg.plan, None, R.ZEROCOPY, seq, s)
+            ok, _ = R.rdev_recv_polling_async(dev, tg.plan, ids, base, s, c)
+            assert ok
+            cons.synchronize()
+            torch.cuda.synchronize()
+            tt.append((time.perf_counter() - t0) * 1e6)
+        tg.close()
+        grouped[f"flag_groups_{G}"] = round(sorted(tt[2:])[len(tt[2:]) // 2], 1)
     med = lambda v: sorted(v[2:])[len(v[2:]) // 2]
     return {"sends_per_iteration": len(ids), "end_of_set_event_us": round(med(t_event), 1),
-            "polling_async_us": round(med(t_async), 1), "gain": round(med(t_event) / med(t_async), 3)}
+            "polling_async_us": round(med(t_async), 1), "gain": round(med(t_event) / med(t_async), 3),
+            "one_batched_write_polling_async_us": grouped}
 
 
 def queues_leg(R, torch, W, dev, wl, opts, spin, iters=30):
@@ -362,7 +384,7 @@ def main():
     rotate = a.rotate or max(2, -(-(1 << 30) // max(2 * payload, 1)))
     rotate = min(rotate, 64)
     dev = R.rdev_open(0)
-    opts = dict(chunk_bytes=a.chunk_bytes, small_bytes=a.small_bytes)
+    opts = dict(chunk_bytes=a.chunk_bytes, small_bytes=a.small_bytes, flag_groups=a.flag_groups)
     images = W.fill_sources(wl, 0)
     sets = [TransferSet(R, torch, W, dev, wl, images, opts) for _ in range(rotate)]
     del images

@@ -120,6 +120,12 @@ typedef struct {
                                    into fragments, each with header information for re-assembly): 0 = every payload
                                    in one piece; otherwise a multiple of 16, and every payload travels as
                                    ceil(bytes / rpc_frag_bytes) fragments, each behind a 32-byte rdev_frag header */
+    uint32_t flag_groups;       /* whole-plan transfers run as this many launches over consecutive tensors of about
+                                   equal bytes, each followed by the flags of its tensors, so that early tensors
+                                   can be consumed while later ones are still moving (section 3.2: one flag per
+                                   tensor); 0 or 1 = one launch, all flags at its end.  Each extra group costs one
+                                   launch gap. */
+    uint32_t _reserved;
 } rdev_plan_opts;
 
 /* Fragment header of the RPC modes (little endian, 32 bytes), followed by the

@@ -114,6 +114,11 @@ struct rdev_plan_s {
     uint32_t *h_flags = nullptr, *d_flags_view = nullptr;
     // whole-plan deliveries are announced to the host by one word: h_flags[2*n] holds the token of the
     // last one completed; a static tensor is ready when that token differs from the one it consumed
+    // With flag_groups = G the static tensors (plan order) form G consecutive groups of about equal bytes;
+    // group g has its own launch, its own slice of the flag table and its own token word h_batch[g].
+    struct Group { uint32_t first_block = 0, n_blocks = 0, first_flag = 0, n_flags = 0; };
+    std::vector<Group> groups;
+    std::vector<uint32_t> group_of;                  // per index (static tensors)
     uint32_t *h_batch = nullptr, *d_batch_view = nullptr;
     uint32_t issued_token = 0;
     uint32_t seq_ring[16] = {0};
@@ -205,13 +210,13 @@ uint8_t *arena_ptr(rdev_plan_t *plan, uint32_t arena, uint64_t off) { return pla
 uint32_t static_ready(const rdev_plan_t *plan, uint32_t i) {
     const uint32_t v = __atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE);
     if (v) return v;
-    const uint32_t tok = __atomic_load_n(plan->h_batch, __ATOMIC_ACQUIRE);
+    const uint32_t tok = __atomic_load_n(plan->h_batch + plan->group_of[i], __ATOMIC_ACQUIRE);
     return tok != plan->consumed_token[i] ? plan->seq_ring[tok & 15] : 0;
 }
 
 void static_consume(rdev_plan_t *plan, uint32_t i) {
     __atomic_store_n(&plan->h_flags[2 * i], 0u, __ATOMIC_RELEASE);
-    plan->consumed_token[i] = __atomic_load_n(plan->h_batch, __ATOMIC_ACQUIRE);
+    plan->consumed_token[i] = __atomic_load_n(plan->h_batch + plan->group_of[i], __ATOMIC_ACQUIRE);
 }
 
 uint32_t next_token(rdev_plan_t *plan, uint32_t seq) {
@@ -224,6 +229,15 @@ rdev_status launch_check(const char *what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(RDEV_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
     return RDEV_OK;
+}
+
+// flags of one group (in-arena words <- seq, the group's host word <- token)
+rdev_status launch_group_flags(rdev_plan_t *plan, uint32_t g, uint32_t seq, uint32_t token, hipStream_t s) {
+    const rdev_plan_s::Group &gr = plan->groups[g];
+    if (!gr.n_flags) return RDEV_OK;
+    hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((gr.n_flags + 255) / 256), dim3(256), 0, s,
+                       plan->d_flags.ptr + gr.first_flag, gr.n_flags, seq, plan->d_batch_view + g, token);
+    return launch_check("flag_table_kernel");
 }
 
 // cut one tensor into work items
@@ -479,6 +493,9 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
     if (o.flags & ~(uint32_t)RDEV_PLAN_CHECK_BUSY) return fail(RDEV_E_INVAL, "unknown plan flags");
     if (o.rpc_frag_bytes % 16 || o.rpc_frag_bytes > 0xFFFFFFF0ull) return fail(RDEV_E_INVAL, "rpc_frag_bytes must be a multiple of 16 below 4 GiB");
 
+    if (!o.flag_groups) o.flag_groups = 1;
+    if (o.flag_groups > 1024) return fail(RDEV_E_INVAL, "flag_groups must be at most 1024");
+
     std::unique_ptr<rdev_plan_t> plan(new rdev_plan_t());
     plan->dev = dev;
     plan->opts = o;
@@ -518,6 +535,23 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
     }
     plan->polled.resize(plan->n_dyn);
     plan->polled_valid.assign(plan->n_dyn, 0);
+    {   // groups: cut the static tensors, in plan order, where the running byte count passes k/G of the total
+        uint64_t total = 0, run = 0;
+        for (uint32_t i = 0; i < n; ++i) if (plan->pl[i].kind == RDEV_STATIC) total += plan->pl[i].bytes;
+        const uint32_t G = o.flag_groups;
+        plan->groups.assign(G, rdev_plan_s::Group());
+        plan->group_of.assign(n, 0);
+        uint32_t g = 0, flag_i = 0;
+        for (uint32_t i = 0; i < n; ++i) {
+            if (plan->pl[i].kind != RDEV_STATIC) continue;
+            while (g + 1 < G && total && run >= (__uint128_t)total * (g + 1) / G) ++g;
+            plan->group_of[i] = g;
+            if (!plan->groups[g].n_flags) plan->groups[g].first_flag = flag_i;
+            plan->groups[g].n_flags++;
+            run += plan->pl[i].bytes;
+            ++flag_i;
+        }
+    }
 
     dev->n_plans++;              // from here on destroy_plan() undoes everything
     rdev_plan_t *raw = plan.release();
@@ -528,7 +562,7 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
         };
         hipError_t e = hipSetDevice(dev->hip_device);
         if (e != hipSuccess) return bail(e, "hipSetDevice");
-        const size_t nflags = 2 * (size_t)n + 2;
+        const size_t nflags = 2 * (size_t)n + 2 + o.flag_groups;
         e = hipHostMalloc((void **)&raw->h_flags, nflags * sizeof(uint32_t), hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { raw->h_flags = nullptr; return bail(e, "hipHostMalloc(flags)"); }
         std::memset(raw->h_flags, 0, nflags * sizeof(uint32_t));
@@ -611,16 +645,22 @@ rdev_status rdev_plan_bind_sources(rdev_plan_t *plan, const void *const *src_ptr
             return fail(RDEV_E_OVERLAP, "source of tensor " + std::to_string(p.tensor_id) + " overlaps its destination");
     }
     // descriptor table (section 3.4: the sender keeps each destination address with the sending node)
-    std::vector<Item> items, subs, pending;
-    for (uint32_t i = 0; i < n; ++i) {
-        const rdev_placement &p = plan->pl[i];
-        if (p.kind != RDEV_STATIC || !locs[i].bound) continue;
-        const uint8_t *s = plan->dev->arenas[locs[i].arena].base + locs[i].offset;
-        cut_items(s, arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, i, plan->opts.chunk_bytes,
-                  plan->opts.small_bytes, items, subs, pending);
+    std::vector<Item> items, subs;
+    for (uint32_t g = 0; g < plan->groups.size(); ++g) {
+        std::vector<Item> gi, pending;
+        for (uint32_t i = 0; i < n; ++i) {
+            const rdev_placement &p = plan->pl[i];
+            if (p.kind != RDEV_STATIC || !locs[i].bound || plan->group_of[i] != g) continue;
+            const uint8_t *s = plan->dev->arenas[locs[i].arena].base + locs[i].offset;
+            cut_items(s, arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, i, plan->opts.chunk_bytes,
+                      plan->opts.small_bytes, gi, subs, pending);
+        }
+        flush_small(gi, subs, pending);
+        xcd_order(gi);
+        plan->groups[g].first_block = (uint32_t)items.size();
+        plan->groups[g].n_blocks = (uint32_t)gi.size();
+        items.insert(items.end(), gi.begin(), gi.end());
     }
-    flush_small(items, subs, pending);
-    xcd_order(items);
     if (items.size() > 0x7fffffffull) return fail(RDEV_E_INVAL, "too many work items for one launch; raise chunk_bytes");
     if (plan->dev->gpu()) {
         HIP_TRY(hipSetDevice(plan->dev->hip_device));
@@ -783,7 +823,6 @@ rdev_status check_busy_all(rdev_plan_t *plan) {
 rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipStream_t s) {
     if (!plan->copy_tables) RDEV_TRY(build_copy_tables(plan));
     RDEV_TRY(check_busy_all(plan));
-    const uint32_t grid_tbl = (plan->n_static + 255) / 256;
     if (mode == RDEV_SENDERCOPY) {
         if (plan->stage_end > plan->send_buf.bytes) return fail(RDEV_E_NOMEM, "staging buffer too small");
         std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
@@ -796,9 +835,8 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
             RDEV_TRY(launch_check("copy_table_kernel(write)"));
         }
         if (plan->n_static) {
-            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(grid_tbl), dim3(256), 0, s, plan->d_flags.ptr,
-                               plan->n_static, seq, plan->d_batch_view, next_token(plan, seq));
-            RDEV_TRY(launch_check("flag_table_kernel"));
+            const uint32_t token = next_token(plan, seq);
+            for (uint32_t g = 0; g < plan->groups.size(); ++g) RDEV_TRY(launch_group_flags(plan, g, seq, token, s));
         }
         return RDEV_OK;
     }
@@ -844,10 +882,16 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
                                (uint32_t)plan->opts.chunk_bytes);
             RDEV_TRY(launch_check("unpack_table_kernel"));
         }
-        hipLaunchKernelGGL(rdev::rpc_flag_kernel, dim3(grid_tbl), dim3(256), 0, s, plan->d_flags.ptr,
-                           wire ? plan->d_msg_recv.ptr : plan->d_msg_send.ptr, plan->n_static, plan->d_batch_view,
-                           next_token(plan, seq));
-        RDEV_TRY(launch_check("rpc_flag_kernel"));
+        const uint32_t token = next_token(plan, seq);
+        for (uint32_t g = 0; g < plan->groups.size(); ++g) {
+            const rdev_plan_s::Group &gr = plan->groups[g];
+            if (!gr.n_flags) continue;
+            hipLaunchKernelGGL(rdev::rpc_flag_kernel, dim3((gr.n_flags + 255) / 256), dim3(256), 0, s,
+                               plan->d_flags.ptr + gr.first_flag,
+                               (wire ? plan->d_msg_recv.ptr : plan->d_msg_send.ptr) + gr.first_flag, gr.n_flags,
+                               plan->d_batch_view + g, token);
+            RDEV_TRY(launch_check("rpc_flag_kernel"));
+        }
     }
     // where each tensor went (for rdev_poll), and the heap pointers
     for (uint32_t i = 0; i < plan->pl.size(); ++i) {
@@ -900,18 +944,19 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
     if (!plan->bound_all) return fail(RDEV_E_STATE, "not every static tensor has a bound source");
     std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
     RDEV_TRY(check_busy_all(plan));
-    if (plan->n_blocks) {
-        const bool timed = plan->ev_used < plan->ev_start.size() && (plan->ev_count++ % plan->ev_every) == 0;
-        if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
-        hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_blocks), dim3(rdev::kBlockThreads), 0, s,
-                           plan->d_items.ptr, plan->d_subs.ptr);
-        RDEV_TRY(launch_check("copy_table_kernel"));
-        if (timed) HIP_TRY(hipEventRecord(plan->ev_stop[plan->ev_used++], s));
-    }
-    if (plan->n_static) {
-        hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
-                           plan->d_flags.ptr, plan->n_static, seq, plan->d_batch_view, next_token(plan, seq));
-        RDEV_TRY(launch_check("flag_table_kernel"));
+    const uint32_t token = plan->n_static ? next_token(plan, seq) : 0;
+    for (uint32_t g = 0; g < plan->groups.size(); ++g) {
+        const rdev_plan_s::Group &gr = plan->groups[g];
+        if (gr.n_blocks) {
+            // the timing bracket covers the launch of the first group (the only one unless flag_groups > 1)
+            const bool timed = g == 0 && plan->ev_used < plan->ev_start.size() && (plan->ev_count++ % plan->ev_every) == 0;
+            if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
+            hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(gr.n_blocks), dim3(rdev::kBlockThreads), 0, s,
+                               plan->d_items.ptr + gr.first_block, plan->d_subs.ptr);
+            RDEV_TRY(launch_check("copy_table_kernel"));
+            if (timed) HIP_TRY(hipEventRecord(plan->ev_stop[plan->ev_used++], s));
+        }
+        RDEV_TRY(launch_group_flags(plan, g, seq, token, s));
     }
     return RDEV_OK;
 }
@@ -929,9 +974,8 @@ static rdev_status write_dma_mode(rdev_plan_t *plan, uint32_t seq, hipStream_t s
                                p.bytes, hipMemcpyDeviceToDevice, s));
     }
     if (plan->n_static) {
-        hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
-                           plan->d_flags.ptr, plan->n_static, seq, plan->d_batch_view, next_token(plan, seq));
-        RDEV_TRY(launch_check("flag_table_kernel"));
+        const uint32_t token = next_token(plan, seq);
+        for (uint32_t g = 0; g < plan->groups.size(); ++g) RDEV_TRY(launch_group_flags(plan, g, seq, token, s));
     }
     return RDEV_OK;
 }

@@ -50,7 +50,7 @@ class Placement(C.Structure):
 class PlanOpts(C.Structure):
     _fields_ = [("align", C.c_uint64), ("max_static_bytes", C.c_uint64), ("dyn_heap_bytes", C.c_uint64),
                 ("chunk_bytes", C.c_uint64), ("small_bytes", C.c_uint32), ("flags", C.c_uint32),
-                ("rpc_frag_bytes", C.c_uint64)]
+                ("rpc_frag_bytes", C.c_uint64), ("flag_groups", C.c_uint32), ("_reserved", C.c_uint32)]
 
 
 class Meta(C.Structure):
@@ -200,9 +200,10 @@ def make_desc(tensor_id: int, dtype: int, dims: Sequence[int], dst_arena: int) -
 
 def rdev_plan(dev: int, descs: Sequence[TensorDesc], align: int = 0, max_static_bytes: int = 0,
               dyn_heap_bytes: int = 0, chunk_bytes: int = 0, small_bytes: int = 0, flags: int = 0,
-              rpc_frag_bytes: int = 0) -> int:
+              rpc_frag_bytes: int = 0, flag_groups: int = 0) -> int:
     arr = (TensorDesc * max(len(descs), 1))(*descs)
-    o = PlanOpts(align, max_static_bytes, dyn_heap_bytes, chunk_bytes, small_bytes, flags, rpc_frag_bytes)
+    o = PlanOpts(align, max_static_bytes, dyn_heap_bytes, chunk_bytes, small_bytes, flags, rpc_frag_bytes,
+                 flag_groups, 0)
     h = _P()
     _check(lib().rdev_plan(dev, arr, len(descs), C.byref(o), C.byref(h)))
     return h.value

@@ -21,7 +21,7 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 class GpuRun:
     def __init__(self, wl, variant=0, align=256, heap=0, max_static=0, extra_arenas=(), chunk_bytes=0,
-                 small_bytes=0, flags=0, bind=True, rpc_frag_bytes=0):
+                 small_bytes=0, flags=0, bind=True, rpc_frag_bytes=0, flag_groups=0):
         self.wl = wl
         self.dev = R.rdev_open(0)
         self.src_images = W.fill_sources(wl, variant)
@@ -38,7 +38,7 @@ class GpuRun:
                       for i, t in enumerate(wl.tensors)]
         self.plan = R.rdev_plan(self.dev, self.descs, align=align, max_static_bytes=max_static,
                                 dyn_heap_bytes=heap, chunk_bytes=chunk_bytes, small_bytes=small_bytes, flags=flags,
-                                rpc_frag_bytes=rpc_frag_bytes)
+                                rpc_frag_bytes=rpc_frag_bytes, flag_groups=flag_groups)
         self.src_ptrs = [self.send_t[t.src_arena].data_ptr() + t.src_offset if t.is_static else None
                          for t in wl.tensors]
         if bind:

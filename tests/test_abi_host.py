@@ -168,6 +168,7 @@ def test_error_paths():
     assert _status(R.rdev_plan, dev, [d9]) == R.E_INVAL
     assert _status(R.rdev_plan, dev, [R.make_desc(0, f32, (1,), ids[0])], chunk_bytes=1000) == R.E_INVAL
     assert _status(R.rdev_plan, dev, [R.make_desc(0, f32, (1,), ids[0])], rpc_frag_bytes=100) == R.E_INVAL
+    assert _status(R.rdev_plan, dev, [R.make_desc(0, f32, (1,), ids[0])], flag_groups=5000) == R.E_INVAL
     # zero-size and scalar tensors are legal
     plan = R.rdev_plan(dev, [R.make_desc(0, f32, (), ids[0]), R.make_desc(1, f32, (4, 0), ids[0]),
                              R.make_desc(2, R.U8, (1 << 40, 0, 1 << 40), ids[0])])

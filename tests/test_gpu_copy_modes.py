@@ -71,6 +71,10 @@ def test_copy_modes_mixed_sets(seed):
     _run_modes(W.small_mixed(seed, n=40, max_bytes=90000, n_recv=3, gran=1))
 
 
+def test_copy_modes_with_flag_groups():
+    _run_modes(W.small_mixed(26, n=25, max_bytes=50000, n_recv=2, gran=2), iters=1, flag_groups=3)
+
+
 def test_copy_modes_tiny_cutting():
     _run_modes(W.small_mixed(24, n=20, max_bytes=20000, n_recv=2, gran=4), iters=1, chunk_bytes=1024, small_bytes=128)
 

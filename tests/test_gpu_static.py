@@ -69,6 +69,16 @@ def test_result_independent_of_work_cutting(chunk, small):
     _run_static(wl, iters=1, chunk_bytes=chunk, small_bytes=small)
 
 
+@pytest.mark.parametrize("groups", [2, 5, 64])
+def test_flag_groups(groups):
+    # several launches per whole-plan transfer, each followed by the flags of its tensors: same images
+    _run_static(W.small_mixed(78, n=30, max_bytes=300000, n_recv=2, gran=4), iters=2, flag_groups=groups)
+
+
+def test_flag_groups_vgg():
+    _run_static(W.vgg16(), iters=1, flag_groups=4)
+
+
 @pytest.mark.parametrize("align", [16, 64, 4096])
 def test_alignments(align):
     _run_static(W.small_mixed(5, n=20, max_bytes=9000, n_recv=2, gran=2), iters=1, align=align)
