@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for a plain 256 MiB device-to-device copy (profiles/copy_table_kernel_<workload>.md).
 # Valid only for the kernel sources they were taken with: `hash` covers csrc/kernels.h + csrc/rdev.hip.
 TRAFFIC = {
-    "vgg16": {"hash": "291181ed4509fc9b", "fetch_bytes": 557738360, "write_bytes": 553483472},
-    "inception": {"hash": "291181ed4509fc9b", "fetch_bytes": 969972847, "write_bytes": 962474826},
+    "vgg16": {"hash": "63111cd0cf5321ec", "fetch_bytes": 557738570, "write_bytes": 553489458},
+    "inception": {"hash": "63111cd0cf5321ec", "fetch_bytes": 969973364, "write_bytes": 962497884},
 }
 
 
