@@ -248,8 +248,14 @@ rdev_status rdev_plan_free(rdev_plan_t *plan);
  *                       into the receiver's slot, then the metadata flag = seq;
  *                       the payload stays where it is until the receiver pulls.
  * mode != RDEV_ZEROCOPY takes the whole plan (x == NULL); the copying modes
- * RDEV_RPC2 / RDEV_RPC3 / RDEV_SENDERCOPY need rdev_plan_bind_buffers.  seq >= 1 is the value stored into the flags.
- * The whole batch is validated before anything is enqueued. */
+ * RDEV_RPC2 / RDEV_RPC3 / RDEV_SENDERCOPY need rdev_plan_bind_buffers.
+ * seq >= 1 is the value stored into the flags.
+ * The whole batch is validated before anything is enqueued.  Errors: RDEV_E_STATE
+ * (source not bound, buffers not bound), RDEV_E_RANGE (source outside registered
+ * memory), RDEV_E_OVERLAP, RDEV_E_BUSY (RDEV_PLAN_CHECK_BUSY), RDEV_E_NOMEM
+ * (message buffer or heap of a copying mode), RDEV_E_INVAL, RDEV_E_HIP.
+ * Not to be recorded into a HIP graph: every whole-plan call hands the flag
+ * kernel a fresh delivery token, which a replay would repeat. */
 rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
                              uint32_t mode, uint32_t seq, void *stream);
 
