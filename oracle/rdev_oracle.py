@@ -26,9 +26,9 @@ What is modelled (section numbers are the paper's):
                receive buffer,) parsed and copied into a fresh allocation; and
                the sender-side staging copy variant.
 
-Readings where the paper is silent (alignment 256, 4-byte flag word holding the
-iteration number, 128-byte little-endian record, deterministic bump heap, input
-order placement) are fixed here and listed in the design notes of the project.
+Readings where the paper is silent are fixed here: alignment 256, a 4-byte flag
+word holding the iteration number, a 128-byte little-endian record, a
+deterministic bump heap, placement in input order.
 
 The result is exact: after a transfer every receiver region holds the byte
 string of its source tensor at the planned place and nothing else changed.

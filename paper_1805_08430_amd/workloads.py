@@ -347,7 +347,7 @@ def small_mixed(seed: int, n: int = 12, max_bytes: int = 5000, n_recv: int = 2,
 
 
 # --------------------------------------------------------------------------
-# two more sets shaped after the paper's Table 1 (not among the five graded configs)
+# two more sets shaped after the paper's Table 1
 # --------------------------------------------------------------------------
 def fcn5() -> Workload:
     """FCN-5-shaped: 784 -> 4096 -> 4096 -> 4096 -> 4096 -> 10, five weight/bias
