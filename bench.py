@@ -368,7 +368,7 @@ def cpu_baseline(wl_name: str, seconds: float):
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py: this build measures one GPU only (sender and receiver arenas share one HBM); "
+        print("bench.py: the library moves tensors inside one GPU only (sender and receiver arenas share one HBM); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
