@@ -132,6 +132,29 @@ def test_consumer_and_polling_async_on_gpu():
     mx, ws = O.consume_reduce_max(o.dev, o.plan, big)
     assert _results(res_v, 1)[0] == (0, 77, _bits(mx), ws)             # I7: flag seen => the whole new payload seen
 
+    # the same many times over, several waiting consumers at once, fresh data each round: a flag that
+    # became visible before its payload would show up as a stale checksum
+    R.rdev_poll(g.dev, g.plan, big, R.POLL_CONSUME, g.s)
+    O.poll(o.dev, o.plan, big, consume=True)
+    watch = sorted(ids, key=lambda t: -wl.tensors[t].nbytes)[:4]
+    for rnd in range(12):
+        imgs = W.fill_sources(wl, variant=100 + rnd)
+        g.set_sources(imgs)
+        for sid, img in zip(o.send_ids, imgs):
+            o.image(sid)[:] = img
+        for k, t in enumerate(watch):
+            R.rdev_consume_reduce_max(g.dev, g.plan, t, 50_000_000, base + 24 * k, cons.cuda_stream)
+        R.rdev_write_batch(g.dev, g.plan, [R.make_xfer(t) for t in watch], R.ZEROCOPY, 200 + rnd, g.s)
+        O.static_write(o.dev, o.plan, o.sources, 200 + rnd, tensor_ids=watch)
+        cons.synchronize()
+        got = _results(res_v, len(watch))
+        for k, t in enumerate(watch):
+            mx, ws = O.consume_reduce_max(o.dev, o.plan, t)
+            assert got[k] == (0, 200 + rnd, _bits(mx), ws), (rnd, t)
+            assert R.rdev_poll(g.dev, g.plan, t, R.POLL_CONSUME, g.s)
+            assert O.poll(o.dev, o.plan, t, consume=True)[0]
+        g.stream.synchronize()
+
     # argument checks
     with pytest.raises(R.RdevError) as e:
         R.rdev_consume_reduce_max(g.dev, g.plan, big, 0, base + 4, cons.cuda_stream)
