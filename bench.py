@@ -505,6 +505,14 @@ def main():
         runs.append((time.perf_counter() - r0) / 100 * 1e6)
     out["five_runs_of_100"] = {"us_per_iteration_mean": round(sum(runs) / 5, 2), "min": round(min(runs), 2),
                                "max": round(max(runs), 2)}
+    props = torch.cuda.get_device_properties(0)
+    dev_info = {"name": props.name, "compute_units": props.multi_processor_count,
+                "hbm_bytes": props.total_memory}
+    clk, width = getattr(props, "memory_clock_rate", None), getattr(props, "memory_bus_width", None)
+    if clk and width:      # what the runtime reports; the roofline uses the published 8 TB/s whatever this says
+        dev_info.update(memory_clock_khz=clk, memory_bus_bits=width,
+                        reported_peak_gbs=round(2 * clk * 1e3 * width / 8 / 1e9, 1))
+    out["device"] = dev_info
     for ts in sets:
         ts.close()
     del sets
