@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for a plain 256 MiB device-to-device copy (profiles/copy_table_kernel_<workload>.md).
 # Valid only for the kernel sources they were taken with: `hash` covers csrc/kernels.h + csrc/rdev.hip.
 TRAFFIC = {
-    "vgg16": {"hash": "63111cd0cf5321ec", "fetch_bytes": 557738570, "write_bytes": 553489458},
-    "inception": {"hash": "63111cd0cf5321ec", "fetch_bytes": 969973364, "write_bytes": 962497884},
+    "vgg16": {"hash": "7d7e1eef6a3ae000", "fetch_bytes": 557738304, "write_bytes": 553475899},
+    "inception": {"hash": "7d7e1eef6a3ae000", "fetch_bytes": 969972908, "write_bytes": 962466752},
 }
 
 
@@ -508,10 +508,10 @@ def main():
     props = torch.cuda.get_device_properties(0)
     dev_info = {"name": props.name, "compute_units": props.multi_processor_count,
                 "hbm_bytes": props.total_memory}
-    clk, width = getattr(props, "memory_clock_rate", None), getattr(props, "memory_bus_width", None)
-    if clk and width:      # what the runtime reports; the roofline uses the published 8 TB/s whatever this says
-        dev_info.update(memory_clock_khz=clk, memory_bus_bits=width,
-                        reported_peak_gbs=round(2 * clk * 1e3 * width / 8 / 1e9, 1))
+    info = R.rdev_device_info(dev)
+    # what the runtime reports (2 GHz x 8192 bits on this part; HBM3E moves 4 bits per pin per reported clock,
+    # i.e. 8.19 TB/s); the roofline uses the published 8 TB/s
+    dev_info.update(info)
     out["device"] = dev_info
     for ts in sets:
         ts.close()

@@ -435,6 +435,10 @@ rdev_status rdev_graph_transfers(const rdev_graph_t *g, const uint32_t *partitio
 
 /* ---- measurement -------------------------------------------------------- */
 
+/* What the HIP runtime reports for the device: out[0] = memory clock (kHz),
+ * out[1] = memory bus width (bits), out[2] = compute units, out[3] = L2 cache bytes. */
+rdev_status rdev_device_info(rdev_device_t *dev, uint64_t out[4]);
+
 /* Time the batched copy kernel of whole-plan transfers (x == NULL) with HIP
  * events recorded on the transfer's own stream, directly before and after that
  * kernel (the flag kernel that follows is outside the bracket).  Every

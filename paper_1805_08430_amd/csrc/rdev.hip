@@ -1494,6 +1494,18 @@ rdev_status rdev_tracer_set_get(const rdev_tracer_t *tr, uint32_t i, uint32_t *n
     return RDEV_OK;
 }
 
+rdev_status rdev_device_info(rdev_device_t *dev, uint64_t out[4]) {
+    if (!dev || !out) return fail(RDEV_E_INVAL, "NULL argument");
+    RDEV_TRY(require_gpu(dev));
+    hipDeviceProp_t p;
+    HIP_TRY(hipGetDeviceProperties(&p, dev->hip_device));
+    out[0] = (uint64_t)p.memoryClockRate;
+    out[1] = (uint64_t)p.memoryBusWidth;
+    out[2] = (uint64_t)p.multiProcessorCount;
+    out[3] = (uint64_t)p.l2CacheSize;
+    return RDEV_OK;
+}
+
 rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples, uint32_t every) {
     if (!plan) return fail(RDEV_E_INVAL, "NULL argument");
     plan->ev_every = every ? every : 1;

@@ -123,6 +123,7 @@ SYMBOLS = {
     "rdev_tracer_send": (C.c_int32, [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.POINTER(C.c_uint32)]),
     "rdev_tracer_set_size": (C.c_int32, [_P, C.POINTER(C.c_uint32)]),
     "rdev_tracer_set_get": (C.c_int32, [_P, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]),
+    "rdev_device_info": (C.c_int32, [_P, C.POINTER(C.c_uint64)]),
     "rdev_plan_profile": (C.c_int32, [_P, C.c_uint32, C.c_uint32]),
     "rdev_plan_profile_read": (C.c_int32, [_P, C.POINTER(C.c_float), C.c_uint32, C.POINTER(C.c_uint32)]),
 }
@@ -400,6 +401,12 @@ def rdev_tracer_set(tr: int):
         _check(lib().rdev_tracer_set_get(tr, i, C.byref(a), C.byref(b)))
         out.append((a.value, b.value))
     return out
+
+
+def rdev_device_info(dev: int) -> dict:
+    v = (C.c_uint64 * 4)()
+    _check(lib().rdev_device_info(dev, v))
+    return dict(memory_clock_khz=v[0], memory_bus_bits=v[1], compute_units=v[2], l2_bytes=v[3])
 
 
 def rdev_plan_profile(plan: int, max_samples: int, every: int = 1) -> None:
