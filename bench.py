@@ -505,6 +505,27 @@ def main():
         runs.append((time.perf_counter() - r0) / 100 * 1e6)
     out["five_runs_of_100"] = {"us_per_iteration_mean": round(sum(runs) / 5, 2), "min": round(min(runs), 2),
                                "max": round(max(runs), 2)}
+    if has_dyn:
+        # the dynamic protocol on its own (section 3.3): metadata + flag -> host poll -> allocate + pull -> host poll
+        ts = sets[0]
+        lat = []
+        for k in range(203):
+            xs, _ = ts.dyn_variants[k % len(ts.dyn_variants)]
+            seq += 1
+            torch.cuda.synchronize()
+            d0 = time.perf_counter()
+            R.rdev_dyn_reset(ts.plan)
+            R.rdev_write_batch(dev, ts.plan, xs, R.ZEROCOPY, seq, s2)
+            for t in ts.dyn_ids:
+                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_META | R.POLL_CONSUME, s2))
+            R.rdev_read_batch(dev, ts.plan, ts.dyn_pull, seq, s2)
+            for t in ts.dyn_ids:
+                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, s2))
+            lat.append((time.perf_counter() - d0) * 1e6)
+        lat = sorted(lat[3:])
+        out["dynamic_round_trip_us"] = {"median": round(lat[len(lat) // 2], 2), "min": round(lat[0], 2),
+                                        "p90": round(lat[int(len(lat) * 0.9)], 2), "tensors": len(ts.dyn_ids),
+                                        "payload_bytes_mean": round(dyn_bytes)}
     props = torch.cuda.get_device_properties(0)
     dev_info = {"name": props.name, "compute_units": props.multi_processor_count,
                 "hbm_bytes": props.total_memory}
