@@ -297,6 +297,44 @@ def queues_leg(R, torch, W, dev, wl, opts, spin, iters=30):
     return {"destination_arenas": len(groups), "us_per_iteration": res}
 
 
+def graph_leg(R, torch, W, dev, wl, opts, spin, iters=30):
+    """One send per tensor (the granularity of the paper's send operator) is bound by
+    launches; the same sequence recorded once into a HIP graph and replayed."""
+    images = W.fill_sources(wl, 0)
+    ts = TransferSet(R, torch, W, dev, wl, images, opts)
+    del images
+    ids = [i for i, t in enumerate(wl.tensors) if t.is_static]
+    xs = [[R.make_xfer(i)] for i in ids]
+    st = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):
+        for x in xs:
+            R.rdev_write_batch(dev, ts.plan, x, R.ZEROCOPY, 1, st.cuda_stream)
+    st.synchronize()
+    res = {}
+    for name in ("eager", "graph_replay"):
+        tt = []
+        for it in range(iters + 3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            if name == "eager":
+                for x in xs:
+                    R.rdev_write_batch(dev, ts.plan, x, R.ZEROCOPY, 1, st.cuda_stream)
+            else:
+                with torch.cuda.stream(st):
+                    graph.replay()
+            spin(lambda: all(R.rdev_poll(dev, ts.plan, i) for i in ids))
+            tt.append((time.perf_counter() - t0) * 1e6)
+            for i in ids:
+                R.rdev_poll(dev, ts.plan, i, R.POLL_CONSUME, st.cuda_stream)
+            st.synchronize()
+        res[name + "_us"] = round(sorted(tt[3:])[len(tt[3:]) // 2], 1)
+    del graph
+    ts.close()
+    res["sends"] = len(ids)
+    return res
+
+
 def cpu_baseline(wl_name: str, seconds: float):
     """The CPU checker's static transfer on the same workload, as it stands."""
     import numpy as np
@@ -580,6 +618,7 @@ def main():
         out["tracing"] = tracing_leg(R, torch, dev, wl, s, spin)
         out["consumer_overlap"] = consumer_leg(R, torch, W, dev, wl, opts, s, spin)
         out["queues"] = queues_leg(R, torch, W, dev, wl, opts, spin)
+        out["per_tensor_sends"] = graph_leg(R, torch, W, dev, wl, opts, spin)
     if a.calibrate:
         nb = 256 << 20
         x = torch.ones(nb, dtype=torch.uint8, device="cuda:0")

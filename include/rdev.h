@@ -254,8 +254,10 @@ rdev_status rdev_plan_free(rdev_plan_t *plan);
  * (source not bound, buffers not bound), RDEV_E_RANGE (source outside registered
  * memory), RDEV_E_OVERLAP, RDEV_E_BUSY (RDEV_PLAN_CHECK_BUSY), RDEV_E_NOMEM
  * (message buffer or heap of a copying mode), RDEV_E_INVAL, RDEV_E_HIP.
- * Not to be recorded into a HIP graph: every whole-plan call hands the flag
- * kernel a fresh delivery token, which a replay would repeat. */
+ * A whole-plan call (x == NULL) must not be recorded into a HIP graph: it hands
+ * the flag kernel a fresh delivery token, which a replay would repeat.  Explicit
+ * batches of static tensors launch kernels only and may be recorded and replayed
+ * (consume the flags between replays, as between eager calls). */
 rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
                              uint32_t mode, uint32_t seq, void *stream);
 
