@@ -192,6 +192,22 @@ def test_error_paths():
     R.rdev_close(dev)
 
 
+def test_header_is_plain_c_and_usable_from_c(tmp_path):
+    """include/rdev.h compiles as C99 with gcc, and a C program linked against the
+    library reproduces the hand-computed placement."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no gcc")
+    exe = str(tmp_path / "c_abi_check")
+    libdir = os.path.dirname(R.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c_abi_check.c"), "-o", exe, "-L", libdir, "-lrdev",
+                    "-Wl,-rpath," + libdir], check=True, capture_output=True, text=True)
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0 and "c abi ok" in r.stdout, r.stdout + r.stderr
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(R, "_lib", None)
     monkeypatch.setattr(R, "LIB_PATH", "/nonexistent/librdev.so")
