@@ -169,6 +169,11 @@ typedef struct {
     uint32_t    dtype;              /* dynamic tensors: run-time element type (must equal the planned one) */
     uint32_t    _pad;
     int64_t     dims[RDEV_MAX_DIMS];/* dynamic tensors: run-time dims, all >= 0 */
+    const uint32_t *dim0_dev;       /* dynamic tensors, optional: device pointer to the leading dim, read by the
+                                       metadata kernel when it runs (a size that only the GPU knows, e.g. the count
+                                       rdev_gather_unique_rows produced on the same stream - no host round trip).
+                                       dims[0] is then the caller's upper bound: the source range is validated with
+                                       it and a larger count is cut to it.  NULL = dims[0] is the size. */
 } rdev_xfer;
 
 /* ---- device (section 3.1) ------------------------------------------------ */

@@ -62,6 +62,9 @@ struct MetaBatch {
     uint8_t *slot[kMetaInlineMax];          // receiver slot in the arena
     uint32_t meta_idx[kMetaInlineMax];      // index of the host-visible copy of the record
     uint32_t flag_idx[kMetaInlineMax];      // index of the host-visible metadata flag
+    const uint32_t *dim0_dev[kMetaInlineMax]; // when set: the leading dim is read from this device word at run time
+    uint64_t row_bytes[kMetaInlineMax];     // bytes per unit of the leading dim (used with dim0_dev)
+    uint64_t dim0_max[kMetaInlineMax];      // the caller's bound on the leading dim (used with dim0_dev)
     uint32_t n;
     uint32_t seq;
 };
@@ -187,7 +190,15 @@ __global__ __launch_bounds__(64) void meta_write_kernel(MetaBatch b, uint32_t *m
     uint32_t *slot = (uint32_t *)b.slot[k];
     uint32_t *host = (uint32_t *)(mirror_meta + b.meta_idx[k]);
     if (t < 30) {
-        const uint32_t w = b.words[k][t];
+        uint32_t w = b.words[k][t];
+        if (b.dim0_dev[k] && (t == 2 || t == 3 || t == 6 || t == 7)) {
+            // a size known only on the device: leading dim (words 6,7) and bytes (words 2,3) are filled in here;
+            // a count beyond the caller's bound is cut to the bound
+            uint64_t d0 = *b.dim0_dev[k];
+            if (d0 > b.dim0_max[k]) d0 = b.dim0_max[k];
+            const uint64_t v = (t < 4) ? d0 * b.row_bytes[k] : d0;
+            w = (t & 1) ? (uint32_t)(v >> 32) : (uint32_t)v;
+        }
         slot[t] = w;
         host[t] = w;
     }

@@ -1037,6 +1037,8 @@ rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_x
         rdev_status st = rdev::tensor_bytes(x[k].dtype, x[k].ndims, x[k].dims, &nb, err);
         if (st != RDEV_OK) return fail(st, err);
         if (!x[k].src) return fail(RDEV_E_INVAL, "a dynamic tensor needs a source address");
+        if (x[k].dim0_dev && (!x[k].ndims || ((uintptr_t)x[k].dim0_dev & 3)))
+            return fail(RDEV_E_INVAL, "dim0_dev needs a tensor of rank >= 1 and a 4-byte aligned device word");
         Dyn dy{idx, {}, nb, &x[k]};
         RDEV_TRY(locate(dev, x[k].src, nb, &dy.loc));
         if ((plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && __atomic_load_n(&plan->h_flags[2 * idx + 1], __ATOMIC_ACQUIRE))
@@ -1073,6 +1075,11 @@ rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_x
                     mb.slot[mb.n] = arena_ptr(plan, p.dst_arena, p.meta_offset);
                     mb.meta_idx[mb.n] = (uint32_t)plan->dyn_index[dy.idx];
                     mb.flag_idx[mb.n] = 2 * dy.idx + 1;
+                    if (dy.x->dim0_dev) {
+                        mb.dim0_dev[mb.n] = dy.x->dim0_dev;
+                        mb.dim0_max[mb.n] = (uint64_t)dy.x->dims[0];
+                        mb.row_bytes[mb.n] = dy.x->dims[0] ? dy.bytes / (uint64_t)dy.x->dims[0] : 0;
+                    }
                     mb.n++;
                     ++k;
                 }

@@ -62,7 +62,7 @@ class Meta(C.Structure):
 
 class Xfer(C.Structure):
     _fields_ = [("tensor_id", C.c_uint32), ("ndims", C.c_uint32), ("src", C.c_void_p), ("dtype", C.c_uint32),
-                ("_pad", C.c_uint32), ("dims", C.c_int64 * MAX_DIMS)]
+                ("_pad", C.c_uint32), ("dims", C.c_int64 * MAX_DIMS), ("dim0_dev", C.c_void_p)]
 
 
 class ConsumeResult(C.Structure):
@@ -245,9 +245,10 @@ def rdev_plan_free(plan: int) -> None:
     _check(lib().rdev_plan_free(plan))
 
 
-def make_xfer(tensor_id: int, src: Optional[int] = None, dtype: int = 0, dims: Sequence[int] = ()) -> Xfer:
+def make_xfer(tensor_id: int, src: Optional[int] = None, dtype: int = 0, dims: Sequence[int] = (),
+              dim0_dev: Optional[int] = None) -> Xfer:
     x = Xfer()
-    x.tensor_id, x.ndims, x.src, x.dtype = tensor_id, len(dims), src, dtype
+    x.tensor_id, x.ndims, x.src, x.dtype, x.dim0_dev = tensor_id, len(dims), src, dtype, dim0_dev
     for i, v in enumerate(dims[:MAX_DIMS]):
         x.dims[i] = v
     return x

@@ -62,8 +62,8 @@ def test_lstm_sparse_gradient_end_to_end_on_gpu():
     wl = W.lstm()
     table_np = W.lstm_embedding_table()
     heap = 8 << 20
-    g = GpuRun(wl, heap=heap, extra_arenas=(8 << 20,))
-    o = OracleRun(wl, heap=heap, extra_arenas=(8 << 20,))
+    g = GpuRun(wl, heap=heap, extra_arenas=(16 << 20,))
+    o = OracleRun(wl, heap=heap, extra_arenas=(16 << 20,))
     table = torch.from_numpy(table_np).to("cuda:0")
     count = torch.zeros(2, dtype=torch.int32, device="cuda:0")
     src_t, src_id = g.extra_t[0], o.extra_ids[0]
@@ -96,4 +96,34 @@ def test_lstm_sparse_gradient_end_to_end_on_gpu():
             g.wait(t, R.POLL_CONSUME)
             assert O.poll(o.dev, o.plan, t, consume=True, which=O.POLL_DATA)[0]
         _compare_all(g, o, f"iteration {it}")
+    # the same without the host ever learning the count before it sends: the metadata kernel reads it on the device
+    for it in range(3, 6):
+        ids_np = W.lstm_token_ids(it)
+        ids = torch.from_numpy(ids_np.reshape(-1)).to("cuda:0")
+        want_ids, want_rows = O.gather_unique_rows(ids_np, table_np)
+        u = want_ids.size
+        bound = ids.numel() if it != 5 else u - 10                    # round 5: a bound below the count cuts it
+        sent = min(u, bound)
+        R.rdev_dyn_reset(g.plan)
+        O.dyn_reset(o.plan)
+        R.rdev_gather_unique_rows(g.dev, ids.data_ptr(), ids.numel(), W.LSTM_VOCAB, table.data_ptr(), 4096,
+                                  src_t.data_ptr() + ids_off, src_t.data_ptr() + rows_off, count.data_ptr(), g.s)
+        R.rdev_write_batch(g.dev, g.plan,
+                           [R.make_xfer(3, src_t.data_ptr() + ids_off, R.I64, (bound,), count.data_ptr()),
+                            R.make_xfer(4, src_t.data_ptr() + rows_off, R.F32, (bound, 1024), count.data_ptr())],
+                           R.ZEROCOPY, it, g.s)
+        o.image(src_id)[ids_off:ids_off + 8 * u] = want_ids.view(np.uint8)
+        o.image(src_id)[rows_off:rows_off + 4096 * u] = np.ascontiguousarray(want_rows).view(np.uint8).reshape(-1)
+        O.dyn_send(o.dev, o.plan, 3, (src_id, ids_off), O.DTYPE_CODE["i64"], (sent,), it)
+        O.dyn_send(o.dev, o.plan, 4, (src_id, rows_off), O.DTYPE_CODE["f32"], (sent, 1024), it)
+        for t in (3, 4):
+            ok, m = g.wait(t, R.POLL_META | R.POLL_CONSUME, want_meta=True)
+            assert _meta_dict(m) == O.poll(o.dev, o.plan, t, consume=True, which=O.POLL_META)[1]
+            assert m.dims[0] == sent
+        R.rdev_read_batch(g.dev, g.plan, [R.make_xfer(3), R.make_xfer(4)], it, g.s)
+        for t in (3, 4):
+            O.dyn_recv(o.dev, o.plan, t, it)
+            g.wait(t, R.POLL_CONSUME)
+            assert O.poll(o.dev, o.plan, t, consume=True, which=O.POLL_DATA)[0]
+        _compare_all(g, o, f"device-sized iteration {it}")
     g.close()
