@@ -104,18 +104,16 @@ __device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src, uint8
             __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
     } else if ((sa & 3) == 0) {
         const v4u_a4 *s = (const v4u_a4 *)src;
-        for (uint32_t i = tid; i < nvec; i += nth) {
-            v4u r = s[i];
-            __builtin_nontemporal_store(r, d + i);
-        }
+        for (uint32_t i = tid; i < nvec; i += nth)        // same instruction, streaming as well: measured equal to the aligned case
+            __builtin_nontemporal_store((v4u)__builtin_nontemporal_load(s + i), d + i);
     } else {
         const uint32_t m = (uint32_t)(sa & 3);
         const uint32_t sh = m * 8;
         const uint32_t *base = (const uint32_t *)(sa - m);
         for (uint32_t i = tid; i < nvec; i += nth) {
             const uint32_t *w = base + 4 * (size_t)i;
-            v4u lo = *(const v4u_a4 *)w;
-            uint32_t w4 = w[4];
+            v4u lo = __builtin_nontemporal_load((const v4u_a4 *)w);
+            uint32_t w4 = __builtin_nontemporal_load(w + 4);
             v4u r;
             r.x = funnel(lo.x, lo.y, sh);
             r.y = funnel(lo.y, lo.z, sh);
