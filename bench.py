@@ -90,6 +90,7 @@ class TransferSet:
                 need[t.dst_arena] += 512
         heap = 0
         self.dyn_variants = []
+        self.produce = None
         dyn_ids = [i for i, t in enumerate(wl.tensors) if not t.is_static]
         if dyn_ids and not copy_modes:
             variants = dynamic_inputs(W, wl, 4)
@@ -107,6 +108,31 @@ class TransferSet:
                 self.dyn_variants.append((xs, sum(len(p) for _, _, p in v)))
             self.dyn_pull = [R.make_xfer(t) for t in dyn_ids]
             self.dyn_ids = dyn_ids
+            self.produce = None
+            if wl.name == "lstm":
+                # the sparse gradient is produced on the GPU each iteration (distinct ids + their rows), and its
+                # size travels to the metadata kernel through a device word: no host round trip on the sender
+                import numpy as np
+                self.table = torch.from_numpy(W.lstm_embedding_table()).to("cuda:0")
+                self.ids = [torch.from_numpy(W.lstm_token_ids(it).reshape(-1)).to("cuda:0") for it in range(4)]
+                self.count = torch.zeros(2, dtype=torch.int32, device="cuda:0")
+                n_ids = self.ids[0].numel()
+                row_bytes = W.LSTM_WIDTH * 4
+                ids_off, rows_off = 0, (8 * n_ids + 255) // 256 * 256
+                need_src = rows_off + n_ids * row_bytes + 256
+                self.dyn_src2 = torch.empty(need_src, dtype=torch.uint8, device="cuda:0")
+                self.arena_ids.append(R.rdev_register_arena(dev, self.dyn_src2.data_ptr(), self.dyn_src2.numel()))
+                base = self.dyn_src2.data_ptr()
+                xs_dev = [R.make_xfer(dyn_ids[0], base + ids_off, R.I64, (n_ids,), self.count.data_ptr()),
+                          R.make_xfer(dyn_ids[1], base + rows_off, R.F32, (n_ids, W.LSTM_WIDTH), self.count.data_ptr())]
+
+                def produce(k, stream):
+                    ids = self.ids[k % len(self.ids)]
+                    R.rdev_gather_unique_rows(dev, ids.data_ptr(), ids.numel(), W.LSTM_VOCAB, self.table.data_ptr(),
+                                              row_bytes, base + ids_off, base + rows_off, self.count.data_ptr(), stream)
+                    return xs_dev
+                self.produce = produce
+                heap = max(heap, need_src + 4096)
         if copy_modes:                      # fresh allocations of an unpack: the largest arena load, align-padded
             heap = max(sum((t.nbytes + 255) // 256 * 256 for t in wl.static_tensors if t.dst_arena == a)
                        for a in range(wl.n_receiver_arenas)) + 4096
@@ -462,7 +488,7 @@ def main():
             if ts.dyn_variants:
                 # section 3.3: metadata + flag, receiver polls, allocates, pulls, raises payload-complete
                 R.rdev_dyn_reset(ts.plan)
-                xs, _ = ts.dyn_variants[k % len(ts.dyn_variants)]
+                xs = ts.produce(k, s2) if ts.produce else ts.dyn_variants[k % len(ts.dyn_variants)][0]
                 R.rdev_write_batch(dev, ts.plan, xs, R.ZEROCOPY, seq, s2)
                 for t in ts.dyn_ids:
                     spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_META | R.POLL_CONSUME, s2))
@@ -517,8 +543,8 @@ def main():
                    "rotating_sets": rotate, "chunk_bytes": a.chunk_bytes or 16384,
                    "dynamic_payload_bytes_per_iteration": round(dyn_bytes),
                    "step": "write_batch (copy kernel + flag kernel)" +
-                           (" + dynamic tensors: metadata write, metadata poll, allocate + pull, on a second stream"
-                            if has_dyn else "") + " + poll/consume of the previous iteration"},
+                           (" + dynamic tensors: " + ("distinct ids and their rows gathered on the GPU, " if sets[0].produce else "")
+                            + "metadata write, metadata poll, allocate + pull, on a second stream" if has_dyn else "") + " + poll/consume of the previous iteration"},
         "us_per_iteration": round(ms_per_step * 1e3, 2),
         "hbm_gbs_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_frac_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -553,6 +579,8 @@ def main():
             torch.cuda.synchronize()
             d0 = time.perf_counter()
             R.rdev_dyn_reset(ts.plan)
+            if ts.produce:
+                xs = ts.produce(k, s2)
             R.rdev_write_batch(dev, ts.plan, xs, R.ZEROCOPY, seq, s2)
             for t in ts.dyn_ids:
                 spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_META | R.POLL_CONSUME, s2))
