@@ -59,6 +59,7 @@ struct SrcLoc {
     uint64_t offset = 0;
 };
 
+constexpr uint32_t kMaxBlocksPerLaunch = 1u << 21;   // x 1024 lanes stays below 2^32 work-items per launch
 constexpr uint64_t kDefaultChunk = 16384;   // one 16-byte vector per lane of a 1024-lane block
 constexpr uint32_t kDefaultSmall = 4096;    // up to this size a tensor is one wavefront's work
 
@@ -231,6 +232,16 @@ rdev_status launch_check(const char *what) {
     return RDEV_OK;
 }
 
+// one table of work items, in as many launches as the per-launch limit asks for (workgroups are independent)
+rdev_status launch_copy_table(const Item *items, const Item *subs, uint32_t n_blocks, hipStream_t s, const char *what) {
+    for (uint32_t first = 0; first < n_blocks; first += kMaxBlocksPerLaunch) {
+        const uint32_t n = std::min(kMaxBlocksPerLaunch, n_blocks - first);
+        hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(n), dim3(rdev::kBlockThreads), 0, s, items + first, subs);
+        RDEV_TRY(launch_check(what));
+    }
+    return RDEV_OK;
+}
+
 // flags of one group (in-arena words <- seq, the group's host word <- token)
 rdev_status launch_group_flags(rdev_plan_t *plan, uint32_t g, uint32_t seq, uint32_t token, hipStream_t s) {
     const rdev_plan_s::Group &gr = plan->groups[g];
@@ -314,8 +325,17 @@ rdev_status resolve_static(rdev_plan_t *plan, uint32_t idx, const void *src_over
 }
 
 // enqueue copies for up to any number of resolved transfers, kInlineMax per launch
-rdev_status launch_inline_copies(rdev_plan_t *plan, const std::vector<ResolvedStatic> &v, hipStream_t s) {
+rdev_status launch_inline_copies(rdev_plan_t *plan, const std::vector<ResolvedStatic> &in, hipStream_t s) {
     const uint64_t chunk = plan->opts.chunk_bytes;
+    // a transfer that alone exceeds the per-launch limit is cut into pieces that fit
+    const uint64_t piece = (uint64_t)(kMaxBlocksPerLaunch - rdev::kXcds) * chunk;
+    std::vector<ResolvedStatic> v;
+    for (const ResolvedStatic &r : in) {
+        for (uint64_t off = 0; off < r.bytes || (off == 0 && r.bytes == 0); off += piece) {
+            v.push_back(ResolvedStatic{r.idx, r.src + off, r.dst + off, std::min(piece, r.bytes - off)});
+            if (!r.bytes) break;
+        }
+    }
     size_t i = 0;
     while (i < v.size()) {
         rdev::InlineBatch b{};
@@ -324,10 +344,7 @@ rdev_status launch_inline_copies(rdev_plan_t *plan, const std::vector<ResolvedSt
         while (i < v.size() && b.n < rdev::kInlineMax) {
             const uint64_t per = ((v[i].bytes + chunk - 1) / chunk + rdev::kXcds - 1) / rdev::kXcds;
             const uint64_t nb = per * rdev::kXcds;
-            if (blocks + nb > 0x7fffffffull) {
-                if (b.n == 0) return fail(RDEV_E_INVAL, "transfer too large for one launch with this chunk size");
-                break;
-            }
+            if (blocks + nb > kMaxBlocksPerLaunch && b.n) break;      // next launch
             if (nb) {
                 b.e[b.n] = rdev::InlineEnt{v[i].src, v[i].dst, v[i].bytes, (uint32_t)blocks, (uint32_t)per};
                 b.n++;
@@ -661,7 +678,7 @@ rdev_status rdev_plan_bind_sources(rdev_plan_t *plan, const void *const *src_ptr
         plan->groups[g].n_blocks = (uint32_t)gi.size();
         items.insert(items.end(), gi.begin(), gi.end());
     }
-    if (items.size() > 0x7fffffffull) return fail(RDEV_E_INVAL, "too many work items for one launch; raise chunk_bytes");
+    if (items.size() > 0xffffffffull) return fail(RDEV_E_INVAL, "too many work items; raise chunk_bytes");
     if (plan->dev->gpu()) {
         HIP_TRY(hipSetDevice(plan->dev->hip_device));
         HIP_TRY(hipDeviceSynchronize());          // nothing may still read the old tables
@@ -827,12 +844,10 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
         if (plan->stage_end > plan->send_buf.bytes) return fail(RDEV_E_NOMEM, "staging buffer too small");
         std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
         if (plan->n_stage_blocks) {
-            hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_stage_blocks), dim3(rdev::kBlockThreads), 0, s,
-                               plan->d_stage_items.ptr, plan->d_stage_subs.ptr);
-            RDEV_TRY(launch_check("copy_table_kernel(stage)"));
-            hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_stage_blocks), dim3(rdev::kBlockThreads), 0, s,
-                               plan->d_unstage_items.ptr, plan->d_unstage_subs.ptr);
-            RDEV_TRY(launch_check("copy_table_kernel(write)"));
+            RDEV_TRY(launch_copy_table(plan->d_stage_items.ptr, plan->d_stage_subs.ptr, plan->n_stage_blocks, s,
+                                       "copy_table_kernel(stage)"));
+            RDEV_TRY(launch_copy_table(plan->d_unstage_items.ptr, plan->d_unstage_subs.ptr, plan->n_stage_blocks, s,
+                                       "copy_table_kernel(write)"));
         }
         if (plan->n_static) {
             const uint32_t token = next_token(plan, seq);
@@ -865,9 +880,8 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
             RDEV_TRY(launch_check("rpc_frag_header_kernel"));
         }
         if (plan->n_pack_blocks) {
-            hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(plan->n_pack_blocks), dim3(rdev::kBlockThreads), 0, s,
-                               plan->d_pack_items.ptr, plan->d_pack_subs.ptr);
-            RDEV_TRY(launch_check("copy_table_kernel(pack)"));
+            RDEV_TRY(launch_copy_table(plan->d_pack_items.ptr, plan->d_pack_subs.ptr, plan->n_pack_blocks, s,
+                                       "copy_table_kernel(pack)"));
         }
         if (wire) {
             uint8_t *sb = plan->dev->arenas[plan->send_buf.arena_id].base + plan->send_buf.offset;
@@ -875,9 +889,10 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
             std::vector<ResolvedStatic> one{ResolvedStatic{0, sb, rb, plan->msg_total}};
             RDEV_TRY(launch_inline_copies(plan, one, s));
         }
-        if (plan->n_unpack_blocks) {
-            hipLaunchKernelGGL(rdev::unpack_table_kernel, dim3(plan->n_unpack_blocks), dim3(rdev::kBlockThreads), 0, s,
-                               wire ? plan->d_unpack_recv_items.ptr : plan->d_unpack_send_items.ptr,
+        for (uint32_t first = 0; first < plan->n_unpack_blocks; first += kMaxBlocksPerLaunch) {
+            const uint32_t nb = std::min(kMaxBlocksPerLaunch, plan->n_unpack_blocks - first);
+            hipLaunchKernelGGL(rdev::unpack_table_kernel, dim3(nb), dim3(rdev::kBlockThreads), 0, s,
+                               (wire ? plan->d_unpack_recv_items.ptr : plan->d_unpack_send_items.ptr) + first,
                                wire ? plan->d_unpack_recv_subs.ptr : plan->d_unpack_send_subs.ptr, hb,
                                (uint32_t)plan->opts.chunk_bytes);
             RDEV_TRY(launch_check("unpack_table_kernel"));
@@ -951,9 +966,8 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
             // the timing bracket covers the launch of the first group (the only one unless flag_groups > 1)
             const bool timed = g == 0 && plan->ev_used < plan->ev_start.size() && (plan->ev_count++ % plan->ev_every) == 0;
             if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
-            hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(gr.n_blocks), dim3(rdev::kBlockThreads), 0, s,
-                               plan->d_items.ptr + gr.first_block, plan->d_subs.ptr);
-            RDEV_TRY(launch_check("copy_table_kernel"));
+            RDEV_TRY(launch_copy_table(plan->d_items.ptr + gr.first_block, plan->d_subs.ptr, gr.n_blocks, s,
+                                       "copy_table_kernel"));
             if (timed) HIP_TRY(hipEventRecord(plan->ev_stop[plan->ev_used++], s));
         }
         RDEV_TRY(launch_group_flags(plan, g, seq, token, s));

@@ -161,10 +161,12 @@ def test_dynamic_errors_and_heap_exhaustion():
     g.close()
 
 
-def test_large_offsets_and_one_gib_tensor():
+@pytest.mark.parametrize("chunk", [0, 256])
+def test_large_offsets_and_one_gib_tensor(chunk):
     """One 1 GiB tensor placed behind a 4.25 GiB region: offsets beyond 2^32,
-    65536 work items.  The CPU checker runs the same plan; payload, flag and
-    a sample of the surroundings are compared."""
+    65536 work items (4 194 304 with 256-byte items, which takes more than one
+    launch).  The CPU checker runs the same plan; payload, flag and a sample of
+    the surroundings are compared; then the same tensor again as an explicit send."""
     from gpu_harness import to_dev
     gib = 1 << 30
     filler = 4 * gib + (gib >> 2)
@@ -176,7 +178,8 @@ def test_large_offsets_and_one_gib_tensor():
     s_id = R.rdev_register_arena(dev, src_t.data_ptr(), src_t.numel())
     r_id = R.rdev_register_arena(dev, recv_t.data_ptr(), recv_t.numel())
     hold = R.rdev_alloc_region(dev, r_id, filler, 256)
-    plan = R.rdev_plan(dev, [R.make_desc(7, R.U8, (gib,), r_id), R.make_desc(8, R.U8, (33,), r_id)])
+    plan = R.rdev_plan(dev, [R.make_desc(7, R.U8, (gib,), r_id), R.make_desc(8, R.U8, (33,), r_id)],
+                       chunk_bytes=chunk)
     odev = O.Device()
     odev.register_arena(src_np.copy())
     odev.register_arena(np.zeros(arena_bytes, dtype=np.uint8))
@@ -196,6 +199,15 @@ def test_large_offsets_and_one_gib_tensor():
     got = recv_t[lo:].cpu().numpy()
     assert np.array_equal(got, odev.arenas[1].mem[lo:])
     assert int(recv_t[:lo].max().item()) == 0                    # nothing below the plan's block was touched
+    # explicit send of the big tensor from another place in the source
+    assert R.rdev_poll(dev, plan, R.ALL_TENSORS, R.POLL_CONSUME, stream.cuda_stream)
+    R.rdev_write_batch(dev, plan, [R.make_xfer(7, src_t.data_ptr() + 48)], R.ZEROCOPY, 10, stream.cuda_stream)
+    O.poll(odev, opl, 7, consume=True)
+    O.poll(odev, opl, 8, consume=True)
+    O.static_write(odev, opl, {7: (0, 48)}, 10, tensor_ids=[7])
+    stream.synchronize()
+    assert R.rdev_poll(dev, plan, 7) and not R.rdev_poll(dev, plan, 8)
+    assert np.array_equal(recv_t[lo:].cpu().numpy(), odev.arenas[1].mem[lo:])
     R.rdev_plan_free(plan)
     R.rdev_free_region(dev, hold)
     R.rdev_close(dev)
