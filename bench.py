@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for a plain 256 MiB device-to-device copy (profiles/copy_table_kernel_<workload>.md).
 # Valid only for the kernel sources they were taken with: `hash` covers csrc/kernels.h + csrc/rdev.hip.
 TRAFFIC = {
-    "vgg16": {"hash": "56ee605e6ead9a7b", "fetch_bytes": 557738148, "write_bytes": 553468437},
-    "inception": {"hash": "56ee605e6ead9a7b", "fetch_bytes": 969973000, "write_bytes": 962479750},
+    "vgg16": {"hash": "8b4f78ba67514451", "fetch_bytes": 557738619, "write_bytes": 553471771},
+    "inception": {"hash": "8b4f78ba67514451", "fetch_bytes": 969973004, "write_bytes": 962477926},
 }
 
 
