@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for a plain 256 MiB device-to-device copy (profiles/copy_table_kernel_<workload>.md).
 # Valid only for the kernel sources they were taken with: `hash` covers csrc/kernels.h + csrc/rdev.hip.
 TRAFFIC = {
-    "vgg16": {"hash": "8b4f78ba67514451", "fetch_bytes": 557738619, "write_bytes": 553471771},
-    "inception": {"hash": "8b4f78ba67514451", "fetch_bytes": 969973004, "write_bytes": 962477926},
+    "vgg16": {"hash": "c198eecb778ffc8f", "fetch_bytes": 557738622, "write_bytes": 553477556},
+    "inception": {"hash": "c198eecb778ffc8f", "fetch_bytes": 969972660, "write_bytes": 962475665},
 }
 
 

@@ -1,6 +1,7 @@
-// Device code of the transfer path (gfx950).  Pure data movement: 16-byte
+// Device code (gfx950).  The transfer kernels are pure data movement: 16-byte
 // vector loads/stores, one vector per lane per step, no LDS and no matrix
-// cores.  Completion flags are stored by a separate small kernel that is
+// cores; LDS appears only in the sparse-id producer and the consumer's
+// reduction further down.  Completion flags are stored by a separate small kernel that is
 // enqueued behind the copy on the same stream, so the kernel boundary is the
 // release point (paper section 3.2 needs "flag visible only after the whole
 // tensor"; a NIC gets that from ascending-address writes, a GPU does not).
