@@ -60,7 +60,7 @@ enum {
     RDEV_E_STATE     = -9   /* call out of protocol order (sources not bound, metadata not polled, ...) */
 };
 
-/* element types carried in the metadata record (section 3.3: "the element data type") */
+/* element type codes carried in the metadata record (section 3.3 lists the element type as one of its fields) */
 enum {
     RDEV_U8 = 0, RDEV_I8 = 1, RDEV_I16 = 2, RDEV_I32 = 3, RDEV_I64 = 4,
     RDEV_F16 = 5, RDEV_BF16 = 6, RDEV_F32 = 7, RDEV_F64 = 8

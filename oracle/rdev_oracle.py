@@ -55,8 +55,8 @@ META_BYTES = 128
 DEFAULT_ALIGN = 256
 FLAG_BYTES = 4
 
-# element type codes of the metadata record (own enumeration; the paper only
-# says the record carries "the element data type")
+# element type codes of the metadata record (own enumeration; section 3.3 only
+# lists the element type among the record's fields)
 DTYPE_CODE = {"u8": 0, "i8": 1, "i16": 2, "i32": 3, "i64": 4, "f16": 5, "bf16": 6, "f32": 7, "f64": 8}
 DTYPE_SIZE = {0: 1, 1: 1, 2: 2, 3: 4, 4: 8, 5: 2, 6: 2, 7: 4, 8: 8}
 

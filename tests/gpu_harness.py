@@ -21,7 +21,7 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 class GpuRun:
     def __init__(self, wl, variant=0, align=256, heap=0, max_static=0, extra_arenas=(), chunk_bytes=0,
-                 small_bytes=0, flags=0, bind=True, rpc_frag_bytes=0, flag_groups=0):
+                 small_bytes=0, flags=0, bind=True, rpc_frag_bytes=0, flag_groups=0, descs_fn=None):
         self.wl = wl
         self.dev = R.rdev_open(0)
         self.src_images = W.fill_sources(wl, variant)
@@ -34,8 +34,9 @@ class GpuRun:
         self.extra_poison = [W.poison(n, wl.seed + 5000 + i) for i, n in enumerate(extra_arenas)]
         self.extra_t = [to_dev(p) for p in self.extra_poison]
         self.extra_ids = [R.rdev_register_arena(self.dev, t.data_ptr(), t.numel()) for t in self.extra_t]
-        self.descs = [R.make_desc(i, R.DTYPE[t.dtype], t.dims, self.recv_ids[t.dst_arena])
-                      for i, t in enumerate(wl.tensors)]
+        # descs_fn(receiver arena ids) supplies the descriptors instead (e.g. the graph analyzer's output)
+        self.descs = descs_fn(self.recv_ids) if descs_fn else \
+            [R.make_desc(i, R.DTYPE[t.dtype], t.dims, self.recv_ids[t.dst_arena]) for i, t in enumerate(wl.tensors)]
         self.plan = R.rdev_plan(self.dev, self.descs, align=align, max_static_bytes=max_static,
                                 dyn_heap_bytes=heap, chunk_bytes=chunk_bytes, small_bytes=small_bytes, flags=flags,
                                 rpc_frag_bytes=rpc_frag_bytes, flag_groups=flag_groups)

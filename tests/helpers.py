@@ -37,7 +37,7 @@ class OracleRun:
     """Sender arenas first (ids 0..S-1), then receiver arenas (S..S+R-1), then
     optional extra buffers: the same registration order the GPU tests use."""
 
-    def __init__(self, wl, variant=0, align=256, heap=0, max_static=0, extra_arenas=()):
+    def __init__(self, wl, variant=0, align=256, heap=0, max_static=0, extra_arenas=(), descs_fn=None):
         self.wl = wl
         self.dev = O.Device()
         self.src_images = W.fill_sources(wl, variant)
@@ -47,7 +47,7 @@ class OracleRun:
         self.recv_ids = [self.dev.register_arena(p.copy()) for p in self.recv_poison]
         self.extra_poison = [W.poison(n, wl.seed + 5000 + i) for i, n in enumerate(extra_arenas)]
         self.extra_ids = [self.dev.register_arena(p.copy()) for p in self.extra_poison]
-        self.descs = oracle_descs(wl, self.recv_ids)
+        self.descs = descs_fn(self.recv_ids) if descs_fn else oracle_descs(wl, self.recv_ids)
         self.plan = O.plan(self.dev, self.descs, align, max_static, heap)
         self.sources = {i: (self.send_ids[t.src_arena], t.src_offset)
                         for i, t in enumerate(wl.tensors) if t.is_static}

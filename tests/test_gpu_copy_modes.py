@@ -15,15 +15,19 @@ pytestmark = pytest.mark.gpu
 MODES = [(R.RPC2, O.MODE_RPC2), (R.RPC3, O.MODE_RPC3), (R.SENDERCOPY, O.MODE_SENDERCOPY)]
 
 
-def _sizes(wl, align=256, frag=0):
+def _sizes(wl, align=256, frag=0, tight=False):
     msg = sum(O.rpc_message_bytes(t.nbytes, frag) for t in wl.static_tensors)
     stage = sum(O.round_up(t.nbytes, align) for t in wl.static_tensors)
+    if tight:       # full-size sets: the heap every arena gets is the largest single arena's need, not the whole set's
+        load = [sum(O.round_up(t.nbytes, align) for t in wl.static_tensors if t.dst_arena == a)
+                for a in range(wl.n_receiver_arenas)]
+        return max(msg, stage) + 512, max(load) + 1024
     return max(msg, stage) + 512, 2 * stage + 1024
 
 
-def _run_modes(wl, iters=2, frag=0, **opts):
+def _run_modes(wl, iters=2, frag=0, modes=None, tight=False, **opts):
     from gpu_harness import GpuRun
-    bufsz, heap = _sizes(wl, frag=frag)
+    bufsz, heap = _sizes(wl, frag=frag, tight=tight)
     if frag:
         opts["rpc_frag_bytes"] = frag
     g = GpuRun(wl, heap=heap, extra_arenas=(bufsz, bufsz), **opts)
@@ -37,7 +41,7 @@ def _run_modes(wl, iters=2, frag=0, **opts):
     static_ids = [i for i, t in enumerate(wl.tensors) if t.is_static]
     seq = 0
     for it in range(iters):
-        for gm, om in MODES + [(R.ZEROCOPY, None), (R.DMA, None)]:
+        for gm, om in (modes or MODES + [(R.ZEROCOPY, None), (R.DMA, None)]):
             seq += 1
             if it or seq > 1:
                 imgs = W.fill_sources(wl, variant=seq)
@@ -90,6 +94,19 @@ def test_fragmented_rpc_inception_one_worker():
 
 def test_copy_modes_inception_two_workers():
     _run_modes(W.inception(2), iters=1)
+
+
+@pytest.mark.parametrize("name", ["inception", "vgg16"])
+def test_copy_modes_full_size(name):
+    """The sets the benchmark times its copying modes on - Inception-shaped x 10 workers -> 10 slots
+    of one server arena, and the VGG-16-shaped set over 8 arenas: what each mode delivered, its message
+    and receive buffers and every fresh allocation, byte for byte."""
+    _run_modes(W.CONFIGS[name](), iters=1, tight=True)
+
+
+@pytest.mark.parametrize("name", ["inception", "vgg16"])
+def test_fragmented_rpc3_full_size(name):
+    _run_modes(W.CONFIGS[name](), iters=1, frag=1 << 20, tight=True, modes=[(R.RPC3, O.MODE_RPC3), (R.RPC2, O.MODE_RPC2)])
 
 
 def test_copy_mode_errors():

@@ -19,35 +19,42 @@ def _meta_dict(m):
                 data_flag=m.data_flag, meta_flag=m.meta_flag)
 
 
-def _dynamic_round(g, o, it, sends, src_arena_idx):
+def _dynamic_round(g, o, it, sends, src_arena_idx, reset=True):
     """sends: list of (tensor_id, dtype name, dims, payload bytes).  Payloads are
-    laid into extra arena `src_arena_idx` at 4-byte (not 16-byte) aligned offsets."""
-    R.rdev_dyn_reset(g.plan)
-    O.dyn_reset(o.plan)
+    laid into extra arena `src_arena_idx` at 4-byte (not 16-byte) aligned offsets.
+    An entry (tensor_id, dtype name, dims, None, (arena id, offset)) names a tensor
+    that already sits in registered memory.  reset=False keeps the heaps as they
+    are (later tensors of the same iteration)."""
+    if reset:
+        R.rdev_dyn_reset(g.plan)
+        O.dyn_reset(o.plan)
     src_id = o.extra_ids[src_arena_idx]
     src_t = g.extra_t[src_arena_idx]
     off = 0
     xs = []
-    for tid, dt, dims, payload in sends:
+    for tid, dt, dims, payload, *where in sends:
+        if payload is None:                     # the tensor already sits in registered memory: (arena id, offset)
+            xs.append((tid, dt, dims, where[0][1], where[0][0]))
+            continue
         off = O.round_up(off, 16) + 4
         o.image(src_id)[off:off + payload.size] = payload
         src_t[off:off + payload.size].copy_(torch.from_numpy(payload))
-        xs.append((tid, dt, dims, off))
+        xs.append((tid, dt, dims, off, src_id))
         off += payload.size
     torch.cuda.synchronize()
-    for tid, dt, dims, _ in xs:
+    for tid, dt, dims, *_ in xs:
         assert not R.rdev_poll(g.dev, g.plan, tid, R.POLL_META)
         with pytest.raises(R.RdevError) as e:
             R.rdev_read_batch(g.dev, g.plan, [R.make_xfer(tid)], it, g.s)      # metadata not polled yet
         assert e.value.status == R.E_STATE
     # sender: metadata + flag for all of them in one call
     R.rdev_write_batch(g.dev, g.plan,
-                       [R.make_xfer(tid, src_t.data_ptr() + so, R.DTYPE[dt], dims) for tid, dt, dims, so in xs],
+                       [R.make_xfer(tid, g.tensor_of(sa).data_ptr() + so, R.DTYPE[dt], dims) for tid, dt, dims, so, sa in xs],
                        R.ZEROCOPY, it, g.s)
-    for tid, dt, dims, so in xs:
-        O.dyn_send(o.dev, o.plan, tid, (src_id, so), O.DTYPE_CODE[dt], dims, it)
+    for tid, dt, dims, so, sa in xs:
+        O.dyn_send(o.dev, o.plan, tid, (sa, so), O.DTYPE_CODE[dt], dims, it)
     # receiver: poll metadata (consume), pull, poll payload flag (consume)
-    for tid, dt, dims, so in xs:
+    for tid, dt, dims, so, sa in xs:
         assert not R.rdev_poll(g.dev, g.plan, tid)                               # payload flag not set yet
         ok, m = g.wait(tid, R.POLL_META | R.POLL_CONSUME, want_meta=True)
         ok2, m2 = O.poll(o.dev, o.plan, tid, consume=True, which=O.POLL_META)
@@ -56,7 +63,7 @@ def _dynamic_round(g, o, it, sends, src_arena_idx):
     _compare_all(g, o, f"round {it}: metadata delivered and consumed")
     R.rdev_read_batch(g.dev, g.plan, [R.make_xfer(tid) for tid, *_ in xs], it, g.s)
     dsts = [O.dyn_recv(o.dev, o.plan, tid, it) for tid, *_ in xs]
-    for (tid, dt, dims, so), dst in zip(xs, dsts):
+    for (tid, dt, dims, so, sa), dst in zip(xs, dsts):
         ok, m = g.wait(tid, 0, want_meta=True)
         ok2, m2 = O.poll(o.dev, o.plan, tid, which=O.POLL_DATA)
         assert ok and ok2 and _meta_dict(m) == m2 and m.dst_offset == dst
@@ -159,6 +166,59 @@ def test_dynamic_errors_and_heap_exhaustion():
         O.dyn_recv(o.dev, o.plan, d1, 1)
     _compare_all(g, o, "after exhaustion")
     g.close()
+
+
+def _run_demoted(wl, max_static, heap, iters=2):
+    """The footprint policy (introduction, item (ii)): tensors of known size above
+    max_static_bytes get a metadata slot instead of a region and travel the
+    dynamic path from where they sit in the sender arena; the rest is written
+    statically.  Both sides must classify alike and end with equal arenas."""
+    from gpu_harness import GpuRun
+    from helpers import placement_dict
+    from test_abi_host import lib_placement_dict
+    g = GpuRun(wl, heap=heap, max_static=max_static, extra_arenas=(4096,))
+    o = OracleRun(wl, heap=heap, max_static=max_static, extra_arenas=(4096,))
+    assert [lib_placement_dict(p) for p in R.placements(g.plan)] == [placement_dict(p) for p in o.plan.placements]
+    kinds = [p.kind for p in o.plan.placements]
+    demoted = [i for i, t in enumerate(wl.tensors) if t.is_static and kinds[i] == O.DYNAMIC]
+    static = [i for i in range(len(wl.tensors)) if kinds[i] == O.STATIC]
+    assert demoted and static and all(wl.tensors[i].nbytes > max_static for i in demoted)
+    assert all(wl.tensors[i].nbytes <= max_static for i in static)
+    _compare_all(g, o, "after plan")
+    for it in range(1, iters + 1):
+        if it > 1:
+            imgs = W.fill_sources(wl, variant=it)
+            g.set_sources(imgs)
+            for sid, img in zip(o.send_ids, imgs):
+                o.image(sid)[:] = img
+        R.rdev_write_batch(g.dev, g.plan, None, R.ZEROCOPY, it, g.s)
+        O.static_write(o.dev, o.plan, o.sources, it)
+        sends = [(i, wl.tensors[i].dtype, tuple(wl.tensors[i].dims), None,
+                  (o.send_ids[wl.tensors[i].src_arena], wl.tensors[i].src_offset)) for i in demoted]
+        for k in range(0, len(sends), 3):                       # a few per round, one heap for the iteration
+            _dynamic_round(g, o, it, sends[k:k + 3], 0, reset=(k == 0))
+        assert g.wait_all()
+        assert R.rdev_poll(g.dev, g.plan, R.ALL_TENSORS, R.POLL_CONSUME, g.s)
+        for i in static:
+            assert O.poll(o.dev, o.plan, i, consume=True)[0]
+        _compare_all(g, o, f"iteration {it}")
+    g.close()
+
+
+def test_known_size_tensors_demoted_by_max_static():
+    wl = W.small_mixed(51, n=30, max_bytes=60000, n_recv=2, gran=4)
+    sizes = sorted(t.nbytes for t in wl.tensors)
+    limit = sizes[len(sizes) * 2 // 3]                           # the largest third goes dynamic
+    heap = sum(O.round_up(t.nbytes, 256) for t in wl.tensors if t.nbytes > limit) + 512
+    _run_demoted(wl, limit, heap)
+
+
+def test_vgg_largest_tensor_demoted():
+    """VGG-16-shaped set with a 64 MiB limit: the 411 MB fc weight and the 67 MB one lose
+    their regions (478 MB less pre-allocated memory) and are pulled on demand."""
+    wl = W.vgg16()
+    heap = max(O.round_up(t.nbytes, 256) for t in wl.tensors) + 512
+    _run_demoted(wl, 64 << 20, heap, iters=1)
 
 
 @pytest.mark.parametrize("chunk", [0, 256])

@@ -143,6 +143,51 @@ def test_explicit_batches_and_pull():
     g.close()
 
 
+@pytest.mark.parametrize("name", ["mixed", "vgg16"])
+def test_one_batch_per_destination_on_its_own_stream(name):
+    """Section 3.1 lets the caller choose the queue a transfer travels on.  Here:
+    one explicit batch per destination arena, each enqueued on a stream of its
+    own, all in flight together; per-tensor flags are polled; every arena must
+    equal the checker's, which moves the same batches one after the other."""
+    from gpu_harness import GpuRun
+    wl = W.vgg16() if name == "vgg16" else W.small_mixed(91, n=64, max_bytes=400000, n_recv=8, gran=1)
+    g, o = GpuRun(wl), OracleRun(wl)
+    batches = {}
+    for i, t in enumerate(wl.tensors):
+        batches.setdefault(t.dst_arena, []).append(i)
+    streams = [torch.cuda.Stream() for _ in batches]
+    for it in range(1, 4):
+        if it > 1:
+            imgs = W.fill_sources(wl, variant=it)
+            g.set_sources(imgs)
+            for sid, img in zip(o.send_ids, imgs):
+                o.image(sid)[:] = img
+        for st, (arena, ids) in zip(streams, sorted(batches.items())):
+            R.rdev_write_batch(g.dev, g.plan, [R.make_xfer(i) for i in ids], R.ZEROCOPY, it, st.cuda_stream)
+        for arena, ids in sorted(batches.items()):
+            O.static_write(o.dev, o.plan, o.sources, it, tensor_ids=ids)
+        for st, (arena, ids) in zip(streams, sorted(batches.items())):
+            for i in ids:                                       # host-visible per-tensor flags, no stream sync
+                for _ in range(5_000_000):
+                    if R.rdev_poll(g.dev, g.plan, i):
+                        break
+                else:
+                    raise AssertionError(f"tensor {i} never became ready")
+        for st in streams:
+            st.synchronize()
+        _compare_all(g, o, f"iteration {it}: delivered over {len(streams)} streams")
+        for st, (arena, ids) in zip(streams, sorted(batches.items())):
+            for i in ids:                                       # the clear travels on the delivery's stream
+                assert R.rdev_poll(g.dev, g.plan, i, R.POLL_CONSUME, st.cuda_stream)
+                assert O.poll(o.dev, o.plan, i, consume=True)[0]
+        for st in streams:
+            st.synchronize()
+        assert not any(R.rdev_poll(g.dev, g.plan, i) for ids in batches.values() for i in ids)
+        _compare_all(g, o, f"iteration {it}: consumed")
+    I.check_flag_order(o.dev.log)
+    g.close()
+
+
 def test_error_paths_on_gpu_device():
     from gpu_harness import GpuRun
     wl = W.small_mixed(3, n=6, max_bytes=5000, n_recv=1)

@@ -262,9 +262,22 @@ def test_copy_modes_deliver_what_zero_copy_delivers(mode):
                     c.recv_poison[k][p.data_offset:p.data_offset + p.nbytes]).all()
         assert (got == want).all()
     if mode == O.MODE_SENDERCOPY:
+        # staging buffer image, byte by byte: tensor k sits at the sum of the align-rounded sizes of the
+        # tensors before it, bare (no header, no padding written); everything else keeps the background
+        want = [int(b) for b in c.extra_poison[0]]
+        cur = send[1]
+        src = c.src_images[0]
+        for t in wl.tensors:
+            for k in range(t.nbytes):
+                want[cur + k] = int(src[t.src_offset + k])
+            cur += (t.nbytes + 255) // 256 * 256
+        assert c.image(c.extra_ids[0]).tolist() == want
+        assert (c.image(c.extra_ids[1]) == c.extra_poison[1]).all()          # the second buffer is not used
+        # and the receiver arenas equal the zero-copy run's, flags included (consumed in c, so consume in z)
+        for p in z.plan.placements:
+            assert O.poll(z.dev, z.plan, p.tensor_id, consume=True)[0]
         for rz, rc in zip(z.recv_ids, c.recv_ids):
-            # flags consumed in c only; compare payload regions
-            pass
+            assert (z.image(rz) == c.image(rc)).all()
     # message buffer image, byte by byte, for the RPC modes
     if mode in (O.MODE_RPC2, O.MODE_RPC3):
         want = [int(b) for b in c.extra_poison[0]]
@@ -288,6 +301,41 @@ def test_copy_modes_deliver_what_zero_copy_delivers(mode):
             assert (c.image(c.extra_ids[1])[recv[1] + n:] == c.extra_poison[1][recv[1] + n:]).all()
         else:
             assert (c.image(c.extra_ids[1]) == c.extra_poison[1]).all()
+
+
+def test_where_a_tensor_is_reported_after_rpc_then_zero_copy_delivery():
+    """A copying-mode delivery lands in a fresh heap allocation and the poll says
+    where; a later zero-copy delivery of the same tensor lands in its
+    pre-allocated region again, so the poll must stop naming the old heap
+    offset (section 3.2: the static region's address never changes; section
+    2.2: an RPC receiver allocates anew for every message)."""
+    wl = W.small_mixed(41, n=5, max_bytes=900, n_recv=1, gran=4)
+    nmsg = sum(O.rpc_message_bytes(t.nbytes) for t in wl.tensors)
+    heap = sum(O.round_up(t.nbytes, 256) for t in wl.tensors) + 256
+    r = OracleRun(wl, heap=heap, extra_arenas=(nmsg + 512,))
+    send = r.dev.alloc_region(r.extra_ids[0], nmsg, 256)
+    sized = [i for i, t in enumerate(wl.tensors) if t.nbytes]
+    O.copy_write(r.dev, r.plan, r.sources, O.MODE_RPC2, 1, send)
+    ap = r.plan.arenas[r.recv_ids[0]]
+    heap_ptr = ap.heap_offset
+    for i, t in enumerate(wl.tensors):
+        ok, meta = O.poll(r.dev, r.plan, i, consume=True)
+        assert ok and meta == {"dst_offset": heap_ptr}                 # batch order, align-rounded bump
+        heap_ptr += O.round_up(t.nbytes, 256)
+    # zero-copy delivery of two of them: those are back in their regions, the others still in the heap
+    back = sized[:2]
+    O.static_write(r.dev, r.plan, r.sources, 2, tensor_ids=back)
+    for i in range(len(wl.tensors)):
+        ok, meta = O.poll(r.dev, r.plan, i)
+        if i in back:
+            assert ok and meta is None                                 # None = "in its static region"
+            p = r.plan.get(i)
+            t = wl.tensors[i]
+            assert (r.image(p.dst_arena)[p.data_offset:p.data_offset + p.nbytes] ==
+                    r.src_images[0][t.src_offset:t.src_offset + t.nbytes]).all()
+        else:
+            assert not ok                                              # consumed above, nothing new arrived
+    assert set(r.plan.rpc_offsets) == set(range(len(wl.tensors))) - set(back)
 
 
 @pytest.mark.parametrize("frag", [16, 48, 1024])
