@@ -266,6 +266,29 @@ rdev_status rdev_plan_free(rdev_plan_t *plan);
 rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
                              uint32_t mode, uint32_t seq, void *stream);
 
+/* For callers that cannot allocate device memory - code recorded under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc: the
+ * RDEV_SENDERCOPY delivery (every tensor copied into a staging buffer, then
+ * written from there into its region, then its flag = seq) with the staging
+ * buffer in a fixed array of RDEV_FIXED_STAGING_BYTES inside the library's
+ * device image, instead of the bound send buffer and the device tables that
+ * rdev_write_batch(RDEV_SENDERCOPY) builds on first use.  Calls no hipMalloc /
+ * hipFree; launches kernels only (descriptors travel in kernel arguments).
+ *   x == NULL, n == 0 : every static tensor of the plan, in plan order, from its bound source.
+ *   otherwise         : the n listed static tensors (x[i].src as in rdev_write_batch).
+ * Tensor k is staged at the sum of round_up(bytes, align) of the tensors before
+ * it; a batch whose staging layout exceeds RDEV_FIXED_STAGING_BYTES is rejected
+ * with RDEV_E_NOMEM and nothing moves.  Completion is announced per tensor (host
+ * word + in-arena flag), as for an explicit rdev_write_batch.
+ * Every call on one GPU uses that GPU's one staging array, whatever device
+ * handle or plan it is made with: calls on the same stream follow each other,
+ * calls that overlap on different streams race on the staging bytes.  The array
+ * keeps the last call's contents; nothing in it needs clearing.
+ * Other errors as rdev_write_batch: RDEV_E_STATE, RDEV_E_RANGE, RDEV_E_OVERLAP, RDEV_E_BUSY, RDEV_E_INVAL, RDEV_E_HIP. */
+#define RDEV_FIXED_STAGING_BYTES (16u << 20)
+rdev_status rdev_write_batch_fixed_staging(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
+                                           uint32_t seq, void *stream);
+
 /* One-sided batched read, receiver side: local region <- remote tensor.
  * Dynamic tensor (section 3.3): its metadata must have been seen by
  * rdev_poll(..., RDEV_POLL_META); storage of round_up(bytes, align) is taken

@@ -85,10 +85,16 @@ struct DevBuf {                               // library-owned device table
 
 }  // namespace
 
+// Staging memory of rdev_write_batch_fixed_staging: part of the library's device image, so that entry
+// point never allocates.  Every GPU the library runs on holds its own copy until the process ends.  In host
+// code this name only stands for the symbol; the device address is looked up once per device in rdev_open.
+static __device__ __align__(256) uint8_t scratch[RDEV_FIXED_STAGING_BYTES];
+
 struct rdev_device_s {
     int hip_device = RDEV_HOST_ONLY;
     std::vector<Arena> arenas;
     int n_plans = 0;
+    uint8_t *fixed_staging = nullptr;     // device address of `scratch` on hip_device
     bool gpu() const { return hip_device >= 0; }
 };
 
@@ -427,8 +433,11 @@ rdev_status rdev_open(rdev_device_t **out, int hip_device) {
         if (hip_device >= n) return fail(RDEV_E_HIP, "no such HIP device");
         HIP_TRY(hipSetDevice(hip_device));
     }
+    uint8_t *staging = nullptr;
+    if (hip_device >= 0) HIP_TRY(hipGetSymbolAddress((void **)&staging, HIP_SYMBOL(scratch)));   // this device's copy
     rdev_device_t *d = new rdev_device_t();
     d->hip_device = hip_device;
+    d->fixed_staging = staging;
     *out = d;
     return RDEV_OK;
 }
@@ -1104,6 +1113,51 @@ rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_x
         }
     }
     return RDEV_OK;
+}
+
+rdev_status rdev_write_batch_fixed_staging(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
+                                           uint32_t seq, void *stream) {
+    if (!dev || !plan || plan->dev != dev) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
+    if ((x == nullptr) != (n == 0)) return fail(RDEV_E_INVAL, "x and n must both be empty or both be given");
+    if (!seq) return fail(RDEV_E_INVAL, "seq must be >= 1");
+    RDEV_TRY(require_gpu(dev));
+    hipStream_t s = (hipStream_t)stream;
+    // the tensors, in order: the whole plan's static tensors, or the listed ones
+    std::vector<std::pair<uint32_t, const void *>> list;
+    if (!x) {
+        for (uint32_t i = 0; i < plan->pl.size(); ++i)
+            if (plan->pl[i].kind == RDEV_STATIC) list.emplace_back(i, nullptr);
+    } else {
+        for (uint32_t k = 0; k < n; ++k) {
+            uint32_t idx;
+            RDEV_TRY(index_of(plan, x[k].tensor_id, &idx));
+            if (plan->pl[idx].kind != RDEV_STATIC) return fail(RDEV_E_INVAL, "the staged write takes static tensors");
+            list.emplace_back(idx, x[k].src);
+        }
+    }
+    // validate everything and lay the staging area out (align-spaced, in batch order) before anything is enqueued
+    const uint64_t A = plan->opts.align;
+    std::vector<ResolvedStatic> stage(list.size()), write(list.size());
+    std::vector<std::pair<uint32_t *, uint32_t>> flags;
+    uint64_t ptr = 0;
+    for (size_t k = 0; k < list.size(); ++k) {
+        ResolvedStatic r;
+        RDEV_TRY(resolve_static(plan, list[k].first, list[k].second, &r));
+        const rdev_placement &p = plan->pl[r.idx];
+        if ((plan->opts.flags & RDEV_PLAN_CHECK_BUSY) && static_ready(plan, r.idx))
+            return fail(RDEV_E_BUSY, "tensor " + std::to_string(p.tensor_id) + " has not been consumed");
+        if (r.bytes > RDEV_FIXED_STAGING_BYTES || ptr > RDEV_FIXED_STAGING_BYTES - r.bytes)
+            return fail(RDEV_E_NOMEM, "batch needs more than the " + std::to_string(RDEV_FIXED_STAGING_BYTES) +
+                                          " bytes of fixed staging memory");
+        stage[k] = ResolvedStatic{r.idx, r.src, dev->fixed_staging + ptr, r.bytes};
+        write[k] = ResolvedStatic{r.idx, dev->fixed_staging + ptr, r.dst, r.bytes};
+        flags.emplace_back((uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset), 2 * r.idx);
+        ptr += (r.bytes + A - 1) & ~(A - 1);
+    }
+    for (const auto &e : list) plan->rpc_valid[e.first] = 0;
+    RDEV_TRY(launch_inline_copies(plan, stage, s));      // sender: tensor -> staging
+    RDEV_TRY(launch_inline_copies(plan, write, s));      // staging -> receiver region (the kernel boundary orders the two)
+    return launch_inline_flags(plan, flags, seq, true, s);
 }
 
 rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n, uint32_t seq,

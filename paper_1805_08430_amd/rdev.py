@@ -98,6 +98,7 @@ SYMBOLS = {
     "rdev_dyn_reset": (C.c_int32, [_P]),
     "rdev_plan_free": (C.c_int32, [_P]),
     "rdev_write_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, C.c_uint32, _P]),
+    "rdev_write_batch_fixed_staging": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
     "rdev_read_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
     "rdev_poll": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, C.POINTER(Meta), _P]),
     "rdev_gather_unique_rows": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P, _P, _P, _P]),
@@ -264,6 +265,15 @@ def rdev_write_batch(dev: int, plan: int, x: Optional[Sequence[Xfer]] = None, mo
                      stream: int = 0) -> None:
     arr, n = _xfers(x)
     _check(lib().rdev_write_batch(dev, plan, arr, n, mode, seq, stream or None))
+
+
+FIXED_STAGING_BYTES = 16 << 20
+
+
+def rdev_write_batch_fixed_staging(dev: int, plan: int, x: Optional[Sequence[Xfer]] = None, seq: int = 1,
+                                   stream: int = 0) -> None:
+    arr, n = _xfers(x)
+    _check(lib().rdev_write_batch_fixed_staging(dev, plan, arr, n, seq, stream or None))
 
 
 def rdev_read_batch(dev: int, plan: int, x: Optional[Sequence[Xfer]] = None, seq: int = 1, stream: int = 0) -> None:
