@@ -74,7 +74,9 @@ enum {
     RDEV_RPC2       = 1,  /* section 2.2: pack header+payload into a message buffer, unpack into a fresh allocation */
     RDEV_RPC3       = 2,  /* section 5.1 (RPC over RDMA): as RPC2 plus a buffer-to-buffer copy in between */
     RDEV_SENDERCOPY = 3,  /* section 5.1 (analysis off): stage into a registered buffer, then zero-copy write */
-    RDEV_DMA        = 4   /* comparison only: one hipMemcpyAsync (device to device) per tensor instead of the batched kernel */
+    RDEV_DMA        = 4   /* comparison only: one hipMemcpyAsync (device to device) per tensor instead of the batched
+                             kernel.  Despite the name no DMA engine is involved: inside one GPU the runtime serves
+                             such a copy with a copy kernel of its own, so this measures per-tensor runtime calls */
 };
 
 enum { RDEV_POLL_CONSUME = 1, RDEV_POLL_META = 2, RDEV_POLL_ARENA = 4 };
@@ -299,6 +301,33 @@ rdev_status rdev_write_batch_fixed_staging(rdev_device_t *dev, rdev_plan_t *plan
 rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
                             uint32_t seq, void *stream);
 
+/* The receiver's half of the dynamic protocol (section 3.3) without the host in
+ * the loop: enqueued on `stream` behind the sender's metadata write (the same
+ * stream, or one ordered after it), the kernels read each listed tensor's record
+ * from its slot, clear the metadata flag, take round_up(bytes, align) from the
+ * arena's dynamic heap in batch order, pull the payload from the sender's
+ * address, record the offset in the slot and raise the payload-complete flag =
+ * seq.  The arena ends up byte for byte as after rdev_poll(RDEV_POLL_META |
+ * RDEV_POLL_CONSUME) + rdev_read_batch; no host poll of the metadata is needed,
+ * and rdev_poll(tensor) later reports the payload as usual.
+ *   x, n : 1..8 dynamic tensors (only tensor_id is read).
+ * The checks the host path makes are made on the device: metadata flag set,
+ * sender range inside a registered arena, heap space, no overlap.  If any entry
+ * fails, nothing of the batch moves and no flag changes; rdev_recv_status tells.
+ * The heap pointers then live on the device until the next rdev_dyn_reset:
+ * rdev_read_batch of dynamic tensors and the RPC modes return RDEV_E_STATE in
+ * between (allocations made through them earlier in the iteration are honoured). */
+rdev_status rdev_read_batch_device(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
+                                   uint32_t seq, void *stream);
+/* How the device-side receives of this plan went.  *calls_made_out = calls of
+ * rdev_read_batch_device so far, *calls_done_out = how many of them the GPU has
+ * finished; *status_out / *entry_out = outcome of the last finished one: RDEV_OK,
+ * RDEV_NOT_READY (entry's metadata flag was not set), RDEV_E_RANGE,
+ * RDEV_E_NOMEM (heap exhausted) or RDEV_E_OVERLAP, and the batch entry it
+ * refers to.  Reads pinned host words; any out pointer may be NULL. */
+rdev_status rdev_recv_status(rdev_plan_t *plan, int32_t *status_out, uint32_t *entry_out, uint32_t *calls_done_out,
+                             uint32_t *calls_made_out);
+
 /* Non-blocking completion test (section 3.2: the receiver polls the flag,
  * clears it, then lets dependants run).  Reads pinned host words that the flag
  * kernel stores with system scope - one word per listed tensor for explicit
@@ -309,8 +338,11 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
  *                   record for rdev_read_batch); otherwise the payload-complete flag.
  *   RDEV_ALL_TENSORS: ready when every static tensor of the plan is.
  * RDEV_POLL_CONSUME clears the flag on success: the host side at once, the
- * in-arena word by a small kernel enqueued on `stream`, which must be the stream
- * the delivery was enqueued on (or one ordered after it).
+ * in-arena word by a small kernel enqueued on `stream`.  That may be the
+ * delivery's stream or a stream of the receiver's own: the host-visible word is
+ * stored after the in-arena words it announces, so the clear cannot overtake
+ * them, and the next delivery of this plan waits for a clear that is still
+ * pending on another stream (an event, checked on the host first).
  * RDEV_POLL_ARENA reads the in-arena word with a synchronous copy instead (slow; for checks).
  * meta_out (host pointer, may be NULL): dynamic tensors - the record as last
  * delivered; static tensors after an RPC-mode delivery - dst_offset of the fresh allocation. */
@@ -352,15 +384,35 @@ typedef struct {
  * in-arena flag is non-zero - acquire loads, at most max_spins of them per
  * workgroup - and then reduces the payload.  max_spins == 0: do not look at the
  * flag at all (the caller has polled it on the host).  out: device pointer, 8-byte
- * aligned; written by kernels on `stream`.  Never waits forever. */
+ * aligned; written by kernels on `stream`.  Never waits forever.  A waiting
+ * consumer that is enqueued BEFORE the delivery only sees it arrive if the two
+ * streams are served by different hardware queues (a process has few of them);
+ * on a shared queue the delivery sits behind the waiter until its spins run out. */
 rdev_status rdev_consume_reduce_max(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id, uint32_t max_spins,
                                     rdev_consume_result *out, void *stream);
 
+/* The same consumer for a list of static tensors in one launch per 32 tensors:
+ * out[i] belongs to tensor_ids[i].  Tensors are cut into 256 KiB units that the
+ * workgroups take in list order, so tensors early in the list are reduced first.
+ * With max_spins > 0 every unit first waits (at most max_spins acquire loads) for
+ * its tensor's in-arena flag; enqueued on a second stream behind a delivery that
+ * is still in flight, one launch then consumes each tensor as its flag comes up
+ * (with flag_groups > 1 while later groups are still moving).  At most 256
+ * workgroups wait at a time; they hold wave slots the copy could use (section
+ * 3.5).  A tensor whose flag does not come up in time keeps status 1.  The flags
+ * are not cleared: consume them with rdev_poll afterwards.  For the waiting to
+ * make progress the delivery must be on another stream, mapped to another
+ * hardware queue, or already enqueued. */
+rdev_status rdev_consume_batch(rdev_device_t *dev, rdev_plan_t *plan, const uint32_t *tensor_ids, uint32_t n,
+                               uint32_t max_spins, rdev_consume_result *out, void *stream);
+
 /* Polling-async reception (section 4): the listed static tensors form a ready
  * queue; the head is polled on the host; if its flag is not set it goes back to
- * the tail, otherwise the flag is consumed (cleared on flag_stream, the stream of
- * the deliveries) and its consumer kernel is launched on consumer_stream, writing
- * out[i] for tensor_ids[i].  Returns RDEV_OK when the queue is empty,
+ * the tail, otherwise the flag is consumed and the op turns asynchronous: its
+ * consumer runs on consumer_stream and writes out[i] for tensor_ids[i].  Ops that
+ * succeed one after the other are launched together (one clear on flag_stream,
+ * one consumer launch) when the next poll fails or the queue is empty.  Returns
+ * RDEV_OK when the queue is empty,
  * RDEV_NOT_READY after max_polls failed polls in total.  *polls_out (may be NULL)
  * = polls made. */
 rdev_status rdev_recv_polling_async(rdev_device_t *dev, rdev_plan_t *plan, const uint32_t *tensor_ids, uint32_t n,

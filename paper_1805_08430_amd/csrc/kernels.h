@@ -51,13 +51,6 @@ struct InlineBatch {
     uint32_t chunk;
 };
 
-struct InlineFlags {
-    uint32_t *arena_flag[kInlineMax];
-    uint32_t mirror_idx[kInlineMax];
-    uint32_t n;
-    uint32_t value;
-};
-
 struct MetaBatch {
     uint32_t words[kMetaInlineMax][30];     // the first 120 bytes of each record
     uint8_t *slot[kMetaInlineMax];          // receiver slot in the arena
@@ -159,26 +152,40 @@ __global__ __launch_bounds__(kBlockThreads) void copy_inline_kernel(InlineBatch 
     copy_span(b.e[k].src + off, b.e[k].dst + off, n, threadIdx.x, kBlockThreads);
 }
 
-// flag <- value for a table of tensors (one lane each, in-arena words).
+// flag <- value for a table of tensors (in-arena words), then ONE host-visible word for the whole table.
 // The payload these flags announce was written by the kernel enqueued before this
-// one on the same stream, so it is already visible when this kernel starts: the
-// stores here need the right scope but no fence of their own, which would cost an
-// L2 write-back per lane.  The host is told with ONE word for the whole table
-// (a delivery token): per-tensor host words would be thousands of separate
-// writes across the host link for the many-small-tensor sets.
-__global__ void flag_table_kernel(const FlagEnt *__restrict__ ents, uint32_t n, uint32_t value,
-                                  uint32_t *batch_word, uint32_t token) {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (batch_word && i == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+// one on the same stream, so it is already visible when this kernel starts.
+// The host is told with one word for the whole table (a delivery token):
+// per-tensor host words would be thousands of separate writes across the host
+// link for the many-small-tensor sets.  One workgroup walks the table, so the
+// token can be stored after every in-arena word: a receiver that has seen the
+// token may clear those words from any other stream without meeting a late store.
+constexpr uint32_t kFlagTableThreads = 1024;
+__global__ __launch_bounds__(kFlagTableThreads) void flag_table_kernel(const FlagEnt *__restrict__ ents, uint32_t n,
+                                                                        uint32_t value, uint32_t *batch_word,
+                                                                        uint32_t token) {
+    for (uint32_t i = threadIdx.x; i < n; i += kFlagTableThreads)
+        __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!batch_word) return;
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+constexpr uint32_t kFlagInlineMax = 32;
+struct InlineFlags {
+    uint32_t *arena_flag[kFlagInlineMax];
+    uint32_t mirror_idx[kFlagInlineMax];
+    uint32_t n;
+    uint32_t value;
+};
+
+// the same for a few tensors named in the kernel arguments, one host-visible word each (stored after the in-arena word)
 __global__ void flag_inline_kernel(InlineFlags f, uint32_t *mirror) {
     const uint32_t i = threadIdx.x;
     if (i >= f.n) return;
     __hip_atomic_store(f.arena_flag[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (mirror)
-        __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Dynamic path, sender side: 120 bytes of metadata into the receiver's slot
@@ -216,6 +223,150 @@ __global__ void post_pull_kernel(PostBatch b, uint32_t *mirror_flags, rdev_meta 
     mirror_meta[b.meta_idx[i]].dst_offset = b.dst_offset[i];
     __hip_atomic_store((uint32_t *)(b.slot[i] + 120), b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(mirror_flags + b.flag_idx[i], b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// ---- dynamic path, receiver side, with the sizes taken on the device (section 3.3) ----
+//
+// The receiver's part of the protocol - see the metadata, clear its flag, allocate
+// storage, pull the payload, raise payload-complete - without a host round trip:
+// the kernels are enqueued behind the sender's metadata write and read the
+// record from the slot themselves.  Allocation is the same bump allocator the
+// host path runs (batch order, round_up(bytes, align) each), so the arena image
+// is the same.  Every workgroup derives the batch's layout from the same memory
+// with the same code; a batch that fails any check moves nothing.
+
+constexpr uint32_t kRecvMax = 8;                 // tensors per launch
+constexpr uint32_t kRecvMaxBlocks = 2048;
+
+struct ArenaEnt {                                // device table of the registered arenas
+    uint8_t *base;
+    uint64_t bytes;
+};
+struct HeapWord {                                // device-resident bump pointer of one arena's dynamic heap
+    uint64_t ptr;                                // relative to the heap's start
+    uint32_t epoch;                              // valid for this iteration number only (rdev_dyn_reset starts a new one)
+    uint32_t _pad;
+};
+struct RecvEnt {
+    uint8_t *slot;                               // the tensor's metadata slot
+    uint8_t *arena_base;                         // base of the receiving arena
+    uint64_t heap_offset;                        // start of its dynamic heap, bytes from the arena base
+    uint64_t heap_bytes;
+    uint64_t heap_ptr_host;                      // what the host path has handed out so far in this iteration
+    uint32_t heap_word;                          // index of the arena's HeapWord
+    uint32_t dst_arena;
+    uint32_t meta_idx, flag_idx;                 // host-visible copies: record, flag pair (2*index)
+};
+struct RecvBatch {
+    RecvEnt e[kRecvMax];
+    uint64_t align;
+    uint32_t n, seq, epoch, chunk, n_arenas, call_id;
+};
+struct RecvLayout {                              // what every workgroup works out for itself
+    const uint8_t *src[kRecvMax];
+    uint8_t *dst[kRecvMax];
+    uint64_t bytes[kRecvMax];
+    uint64_t dst_offset[kRecvMax];               // bytes from the arena base
+    uint64_t new_ptr[kRecvMax];                  // the arena's heap pointer after this entry
+    uint64_t first_chunk[kRecvMax + 1];
+    int32_t status;                              // RDEV_OK, RDEV_NOT_READY (a metadata flag is not set) or an RDEV_E_* code
+    uint32_t bad;                                // entry the status refers to
+};
+
+// Lanes 0..n-1 fetch their record, lane 0 runs the allocator over the batch.  Call with all lanes of the workgroup.
+__device__ __forceinline__ void recv_layout(const RecvBatch &b, const ArenaEnt *__restrict__ arenas,
+                                            const HeapWord *__restrict__ heap, RecvLayout &L) {
+    __shared__ uint64_t s_bytes[kRecvMax], s_src_off[kRecvMax], s_heap[kRecvMax];
+    __shared__ uint32_t s_src_arena[kRecvMax], s_flag[kRecvMax];
+    const uint32_t t = threadIdx.x;
+    if (t < b.n) {
+        const uint8_t *slot = b.e[t].slot;
+        s_flag[t] = __hip_atomic_load((const uint32_t *)(slot + 124), __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+        s_bytes[t] = *(const uint64_t *)(slot + 8);
+        s_src_off[t] = *(const uint64_t *)(slot + 16);
+        s_src_arena[t] = *(const uint32_t *)(slot + 96);
+        const HeapWord h = heap[b.e[t].heap_word];
+        s_heap[t] = h.epoch == b.epoch ? h.ptr : b.e[t].heap_ptr_host;
+    }
+    __syncthreads();
+    if (t == 0) {
+        int32_t st = RDEV_OK;
+        uint32_t bad = 0;
+        uint64_t chunks = 0;
+        for (uint32_t k = 0; k < b.n && st == RDEV_OK; ++k) {
+            bad = k;
+            uint64_t ptr = s_heap[k];
+            for (uint32_t j = 0; j < k; ++j)
+                if (b.e[j].heap_word == b.e[k].heap_word) ptr = L.new_ptr[j];      // same arena earlier in the batch
+            const uint64_t nb = s_bytes[k], need = (nb + b.align - 1) & ~(b.align - 1);
+            if (!s_flag[k]) { st = RDEV_NOT_READY; break; }
+            if (s_src_arena[k] >= b.n_arenas || !arenas[s_src_arena[k]].bytes) { st = RDEV_E_RANGE; break; }
+            const ArenaEnt sa = arenas[s_src_arena[k]];
+            if (s_src_off[k] > sa.bytes || nb > sa.bytes - s_src_off[k]) { st = RDEV_E_RANGE; break; }
+            if (need < nb || ptr > b.e[k].heap_bytes || need > b.e[k].heap_bytes - ptr) { st = RDEV_E_NOMEM; break; }
+            const uint64_t dst_off = b.e[k].heap_offset + ptr;
+            if (nb && s_src_arena[k] == b.e[k].dst_arena && s_src_off[k] < dst_off + nb && dst_off < s_src_off[k] + nb) {
+                st = RDEV_E_OVERLAP;
+                break;
+            }
+            L.src[k] = sa.base + s_src_off[k];
+            L.dst[k] = b.e[k].arena_base + dst_off;
+            L.bytes[k] = nb;
+            L.dst_offset[k] = dst_off;
+            L.new_ptr[k] = ptr + need;
+            L.first_chunk[k] = chunks;
+            chunks += (nb + b.chunk - 1) / b.chunk;
+        }
+        L.first_chunk[b.n] = chunks;
+        if (st != RDEV_OK) L.first_chunk[b.n] = 0;
+        L.status = st;
+        L.bad = bad;
+    }
+    __syncthreads();
+}
+
+// pull: workgroups stride over the chunks of all payloads of the batch
+__global__ __launch_bounds__(kBlockThreads) void recv_pull_kernel(RecvBatch b, const ArenaEnt *__restrict__ arenas,
+                                                                   const HeapWord *__restrict__ heap) {
+    __shared__ RecvLayout L;
+    recv_layout(b, arenas, heap, L);
+    if (L.status != RDEV_OK) return;
+    const uint64_t total = L.first_chunk[b.n];
+    for (uint64_t c = blockIdx.x; c < total; c += gridDim.x) {
+        uint32_t k = 0;
+        while (c >= L.first_chunk[k + 1]) ++k;
+        const uint64_t off = (c - L.first_chunk[k]) * b.chunk;
+        const uint64_t rem = L.bytes[k] - off;
+        copy_span(L.src[k] + off, L.dst[k] + off, rem < b.chunk ? (uint32_t)rem : b.chunk, threadIdx.x, kBlockThreads);
+    }
+}
+
+// behind the pull: record the offsets, consume the metadata flags, move the heap pointers, raise payload-complete;
+// and tell the host how the batch went (status[0] = code, [1] = entry it refers to, [2] = call id, stored last)
+__global__ __launch_bounds__(64) void recv_post_kernel(RecvBatch b, const ArenaEnt *__restrict__ arenas, HeapWord *heap,
+                                                        uint32_t *mirror_flags, rdev_meta *mirror_meta, uint32_t *status) {
+    __shared__ RecvLayout L;
+    recv_layout(b, arenas, heap, L);
+    const uint32_t t = threadIdx.x;
+    if (L.status == RDEV_OK && t < b.n) {
+        uint8_t *slot = b.e[t].slot;
+        *(uint64_t *)(slot + 88) = L.dst_offset[t];
+        mirror_meta[b.e[t].meta_idx].dst_offset = L.dst_offset[t];
+        __hip_atomic_store((uint32_t *)(slot + 124), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // metadata consumed
+        __hip_atomic_store(mirror_flags + b.e[t].flag_idx + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        bool last = true;                                                // last entry of its arena stores the heap pointer
+        for (uint32_t j = t + 1; j < b.n; ++j)
+            if (b.e[j].heap_word == b.e[t].heap_word) last = false;
+        if (last) heap[b.e[t].heap_word] = HeapWord{L.new_ptr[t], b.epoch, 0};
+        __hip_atomic_store((uint32_t *)(slot + 120), b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mirror_flags + b.e[t].flag_idx, b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    __syncthreads();
+    if (t == 0) {
+        status[0] = (uint32_t)L.status;
+        status[1] = L.bad;
+        __hip_atomic_store(status + 2, b.call_id, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
 }
 
 // ---- the copying alternatives the paper argues against (sections 2.2, 5.1) ----
@@ -293,15 +444,16 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_table_kernel(const UItem
     }
 }
 
-// flags of delivered messages: the value is the seq found in each header
-__global__ void rpc_flag_kernel(const FlagEnt *__restrict__ ents, uint8_t *const *__restrict__ hdr_ptrs, uint32_t n,
-                                uint32_t *batch_word, uint32_t token) {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) {
+// flags of delivered messages: the value is the seq found in each header; token last, as in flag_table_kernel
+__global__ __launch_bounds__(kFlagTableThreads) void rpc_flag_kernel(const FlagEnt *__restrict__ ents,
+                                                                      uint8_t *const *__restrict__ hdr_ptrs, uint32_t n,
+                                                                      uint32_t *batch_word, uint32_t token) {
+    for (uint32_t i = threadIdx.x; i < n; i += kFlagTableThreads) {
         const uint32_t seq = ((const rdev_meta *)hdr_ptrs[i])->seq;
         __hip_atomic_store(ents[i].arena_flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (i == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // ---- producer of the sparse case: distinct ids (ascending) and their rows ----
@@ -377,13 +529,82 @@ __device__ __forceinline__ uint32_t f2ord(uint32_t bits) { return bits ^ ((bits 
 __device__ __forceinline__ uint32_t ord2f(uint32_t o) { return o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu); }
 constexpr uint32_t kOrdNegInf = 0x007FFFFFu;     // f2ord(bits of -inf = 0xFF800000)
 
-__global__ void consume_init_kernel(rdev_consume_result *out) {
+__device__ __forceinline__ void consume_init_one(rdev_consume_result *out) {
+    out->status = 1;
+    out->seen_flag = 0;
+    ((uint32_t *)&out->max)[0] = kOrdNegInf;         // holds the ordered key until the last workgroup converts it
+    out->_arrivals = 0;
+    out->word_sum = 0;
+}
+
+__global__ void consume_init_kernel(rdev_consume_result *out, uint32_t n) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) consume_init_one(out + i);
+}
+
+// One workgroup's wait for a tensor's in-arena flag: at most max_spins acquire loads by one lane, the answer
+// shared with the others.  Returns the flag value seen, 0 = gave up.
+__device__ __forceinline__ uint32_t consume_wait(const uint32_t *flag, uint32_t max_spins, uint32_t *s_seen) {
+    __syncthreads();                                    // s_seen may still be read from an earlier wait
     if (threadIdx.x == 0) {
-        out->status = 1;
-        out->seen_flag = 0;
-        ((uint32_t *)&out->max)[0] = kOrdNegInf;     // holds the ordered key until the last workgroup converts it
-        out->_arrivals = 0;
-        out->word_sum = 0;
+        uint32_t v = 0;
+        for (uint32_t k = 0; k < max_spins; ++k) {
+            v = __hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+            if (v) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        *s_seen = v;
+    }
+    __syncthreads();
+    return *s_seen;
+}
+
+// Reduce 16-byte vectors [v0, v1) of payload (lane i takes v0 + i, v0 + i + stride, ...), plus the up to three
+// trailing words when `tail` is set, and merge the workgroup's result into *out; the workgroup that brings the
+// arrival count to `arrivals_needed` publishes the result.  Call with all kConsumeThreads lanes.
+__device__ __forceinline__ void consume_slice(const uint8_t *payload, uint64_t bytes, uint64_t v0, uint64_t v1,
+                                              uint64_t first, uint64_t stride, bool tail, uint32_t seen,
+                                              uint32_t arrivals_needed, rdev_consume_result *out, uint32_t *s_max,
+                                              uint64_t *s_sum) {
+    const v4u *p = (const v4u *)payload;
+    uint32_t m = kOrdNegInf;
+    uint64_t sum = 0;
+    auto take = [&](uint32_t w) {
+        sum += w;
+        if ((w & 0x7FFFFFFFu) <= 0x7F800000u) {         // not a NaN
+            const uint32_t o = f2ord(w);
+            m = o > m ? o : m;
+        }
+    };
+    for (uint64_t i = v0 + first; i < v1; i += stride) {
+        const v4u v = __builtin_nontemporal_load(p + i);
+        take(v.x); take(v.y); take(v.z); take(v.w);
+    }
+    if (tail) {                                          // up to three trailing words
+        const uint32_t nt = (uint32_t)((bytes & 15) >> 2);
+        if (threadIdx.x < nt) take(((const uint32_t *)payload)[(bytes >> 4) * 4 + threadIdx.x]);
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t om = __shfl_down(m, off, 64);
+        const uint64_t os = __shfl_down(sum, off, 64);
+        m = om > m ? om : m;
+        sum += os;
+    }
+    __syncthreads();                                     // s_max / s_sum may still be read from an earlier slice
+    if ((threadIdx.x & 63) == 0) { s_max[threadIdx.x >> 6] = m; s_sum[threadIdx.x >> 6] = sum; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (uint32_t w = 1; w < kConsumeThreads / 64; ++w) { m = s_max[w] > m ? s_max[w] : m; sum += s_sum[w]; }
+        __hip_atomic_fetch_max((uint32_t *)&out->max, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add((unsigned long long *)&out->word_sum, (unsigned long long)sum, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + 1 == arrivals_needed) {               // last one: publish
+            const uint32_t key = __hip_atomic_load((uint32_t *)&out->max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ((uint32_t *)&out->max)[0] = ord2f(key);
+            out->seen_flag = seen;
+            out->status = 0;
+        }
     }
 }
 
@@ -395,58 +616,52 @@ __global__ __launch_bounds__(kConsumeThreads) void consume_reduce_max_kernel(con
     __shared__ uint64_t s_sum[kConsumeThreads / 64];
     uint32_t seen = 0;
     if (max_spins) {
-        if (threadIdx.x == 0) {
-            uint32_t v = 0;
-            for (uint32_t k = 0; k < max_spins; ++k) {
-                v = __hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                if (v) break;
-                __builtin_amdgcn_s_sleep(8);
-            }
-            s_seen = v;
-        }
-        __syncthreads();
-        seen = s_seen;
+        seen = consume_wait(flag, max_spins, &s_seen);
         if (!seen) return;                              // status stays 1: every workgroup leaves
     }
-    const uint64_t nvec = bytes >> 4;
-    const v4u *p = (const v4u *)payload;
-    uint32_t m = kOrdNegInf;
-    uint64_t sum = 0;
-    auto take = [&](uint32_t w) {
-        sum += w;
-        if ((w & 0x7FFFFFFFu) <= 0x7F800000u) {         // not a NaN
-            const uint32_t o = f2ord(w);
-            m = o > m ? o : m;
+    consume_slice(payload, bytes, 0, bytes >> 4, (uint64_t)blockIdx.x * kConsumeThreads + threadIdx.x,
+                  (uint64_t)gridDim.x * kConsumeThreads, blockIdx.x == 0, seen, gridDim.x, out, s_max, s_sum);
+}
+
+// The same for a list of tensors in one launch.  A tensor is cut into units of kConsumeUnitBytes; workgroup w takes
+// units w, w + grid, ... of the whole list in order, so tensors early in the list are reduced first.  With
+// max_spins > 0 each unit first waits (bounded) for its tensor's in-arena flag, which lets one launch follow a
+// delivery that is still in flight: tensors whose flag is up are reduced while later ones are still moving.
+// A unit whose wait runs out is skipped; its tensor's result keeps status 1.  Every workgroup ends.
+constexpr uint32_t kConsumeBatchMax = 32;
+constexpr uint32_t kConsumeUnitBytes = 256 * 1024;
+constexpr uint32_t kConsumeTableMaxBlocks = 256;     // when the kernel may have to wait (waiting workgroups hold wave slots)
+
+struct ConsumeEnt {
+    const uint32_t *flag;
+    const uint8_t *payload;
+    uint64_t bytes;
+    uint32_t first_unit;        // units of the tensors before it in the list
+    uint32_t n_units;           // >= 1 (an empty tensor still gets its result published)
+};
+struct ConsumeBatch {
+    ConsumeEnt e[kConsumeBatchMax];
+    uint32_t n, n_units, max_spins, _pad;
+};
+
+__global__ __launch_bounds__(kConsumeThreads) void consume_table_kernel(ConsumeBatch b, rdev_consume_result *out) {
+    __shared__ uint32_t s_seen;
+    __shared__ uint32_t s_max[kConsumeThreads / 64];
+    __shared__ uint64_t s_sum[kConsumeThreads / 64];
+    uint32_t k = 0;
+    for (uint32_t u = blockIdx.x; u < b.n_units; u += gridDim.x) {
+        while (u >= b.e[k].first_unit + b.e[k].n_units) ++k;          // units ascend, so does the tensor
+        const ConsumeEnt &e = b.e[k];
+        uint32_t seen = 0;
+        if (b.max_spins) {
+            seen = consume_wait(e.flag, b.max_spins, &s_seen);
+            if (!seen) continue;
         }
-    };
-    for (uint64_t i = (uint64_t)blockIdx.x * kConsumeThreads + threadIdx.x; i < nvec; i += (uint64_t)gridDim.x * kConsumeThreads) {
-        const v4u v = __builtin_nontemporal_load(p + i);
-        take(v.x); take(v.y); take(v.z); take(v.w);
-    }
-    if (blockIdx.x == 0) {                               // up to three trailing words
-        const uint32_t tail = (uint32_t)((bytes & 15) >> 2);
-        if (threadIdx.x < tail) take(((const uint32_t *)payload)[nvec * 4 + threadIdx.x]);
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        const uint32_t om = __shfl_down(m, off, 64);
-        const uint64_t os = __shfl_down(sum, off, 64);
-        m = om > m ? om : m;
-        sum += os;
-    }
-    if ((threadIdx.x & 63) == 0) { s_max[threadIdx.x >> 6] = m; s_sum[threadIdx.x >> 6] = sum; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (uint32_t w = 1; w < kConsumeThreads / 64; ++w) { m = s_max[w] > m ? s_max[w] : m; sum += s_sum[w]; }
-        __hip_atomic_fetch_max((uint32_t *)&out->max, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_fetch_add((unsigned long long *)&out->word_sum, (unsigned long long)sum, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        if (prev + 1 == gridDim.x) {                     // last workgroup: publish
-            const uint32_t key = __hip_atomic_load((uint32_t *)&out->max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ((uint32_t *)&out->max)[0] = ord2f(key);
-            out->seen_flag = seen;
-            out->status = 0;
-        }
+        const uint32_t j = u - e.first_unit;
+        const uint64_t nvec = e.bytes >> 4, per = kConsumeUnitBytes / 16;
+        const uint64_t v0 = (uint64_t)j * per, v1 = v0 + per < nvec ? v0 + per : nvec;
+        consume_slice(e.payload, e.bytes, v0, v1, threadIdx.x, kConsumeThreads, j + 1 == e.n_units, seen, e.n_units,
+                      out + k, s_max, s_sum);
     }
 }
 

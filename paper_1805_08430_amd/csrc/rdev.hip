@@ -59,6 +59,8 @@ struct SrcLoc {
     uint64_t offset = 0;
 };
 
+constexpr uint32_t kMaxArenas = 4096;                // arena ids a device hands out (ids are not reused)
+constexpr uint32_t kTokenRing = 1024;                // whole-plan deliveries that may be in flight behind a completed one
 constexpr uint32_t kMaxBlocksPerLaunch = 1u << 21;   // x 1024 lanes stays below 2^32 work-items per launch
 constexpr uint64_t kDefaultChunk = 16384;   // one 16-byte vector per lane of a 1024-lane block
 constexpr uint32_t kDefaultSmall = 4096;    // up to this size a tensor is one wavefront's work
@@ -95,6 +97,7 @@ struct rdev_device_s {
     std::vector<Arena> arenas;
     int n_plans = 0;
     uint8_t *fixed_staging = nullptr;     // device address of `scratch` on hip_device
+    rdev::ArenaEnt *d_arenas = nullptr;   // device copy of (base, bytes) per arena id, kMaxArenas entries (GPU devices)
     bool gpu() const { return hip_device >= 0; }
 };
 
@@ -128,13 +131,28 @@ struct rdev_plan_s {
     std::vector<uint32_t> group_of;                  // per index (static tensors)
     uint32_t *h_batch = nullptr, *d_batch_view = nullptr;
     uint32_t issued_token = 0;
-    uint32_t seq_ring[16] = {0};
+    uint32_t seq_ring[kTokenRing] = {0};             // flag value (seq) of the delivery that carried each recent token
     std::vector<uint32_t> consumed_token;
     rdev_meta *h_meta = nullptr, *d_meta_view = nullptr;
     std::vector<rdev_meta> polled;                   // record seen by the last metadata poll
     std::vector<uint8_t> polled_valid;
+    std::vector<uint32_t> tok_scratch;               // rdev_poll(RDEV_ALL_TENSORS): token observed per tensor
     std::vector<uint64_t> rpc_offset;                // per index: fresh allocation of the last RPC-mode delivery
     std::vector<uint8_t> rpc_valid;
+
+    // receives that take their sizes on the device (rdev_read_batch_device)
+    DevBuf<rdev::HeapWord> d_heap;                   // one bump pointer per destination arena, in map order
+    std::map<uint32_t, uint32_t> heap_word_of;       // destination arena -> index in d_heap
+    uint32_t heap_epoch = 1;                         // iteration number; rdev_dyn_reset starts the next one
+    bool heap_on_device = false;                     // this iteration's allocations are known to the device only
+    uint32_t *h_status = nullptr, *d_status_view = nullptr;   // pinned: code, entry, call id of the last device receive
+    uint32_t recv_calls = 0;
+
+    // the in-arena clear of a consume may travel on another stream than the deliveries (the receiver's own queue)
+    hipStream_t delivery_stream = nullptr;
+    hipStream_t clear_stream = nullptr;
+    hipEvent_t ev_clear = nullptr;
+    bool clear_pending = false;
 
     // optional timing of the batched copy kernel
     std::vector<hipEvent_t> ev_start, ev_stop;
@@ -213,28 +231,71 @@ rdev_status index_of(const rdev_plan_t *plan, uint32_t tensor_id, uint32_t *idx)
 
 uint8_t *arena_ptr(rdev_plan_t *plan, uint32_t arena, uint64_t off) { return plan->dev->arenas[arena].base + off; }
 
-// what a static tensor's completion shows to the host: its flag value, 0 = not ready
-uint32_t static_ready(const rdev_plan_t *plan, uint32_t i) {
+// What a static tensor's completion shows to the host: its flag value, 0 = not ready.
+// *tok_out (may be NULL) = the delivery token this answer was read from; a consume must record exactly
+// that token, so that a delivery landing between the test and the consume is not swallowed.
+// *stale_out (may be NULL) is set when the tensor is ready but so many whole-plan deliveries have been
+// issued since the completed one that its ring slot was recycled: the flag value is then unknown.
+uint32_t static_ready(const rdev_plan_t *plan, uint32_t i, uint32_t *tok_out = nullptr, bool *stale_out = nullptr) {
+    const uint32_t tok = __atomic_load_n(plan->h_batch + plan->group_of[i], __ATOMIC_ACQUIRE);
+    if (tok_out) *tok_out = tok;
     const uint32_t v = __atomic_load_n(&plan->h_flags[2 * i], __ATOMIC_ACQUIRE);
     if (v) return v;
-    const uint32_t tok = __atomic_load_n(plan->h_batch + plan->group_of[i], __ATOMIC_ACQUIRE);
-    return tok != plan->consumed_token[i] ? plan->seq_ring[tok & 15] : 0;
+    if (tok == plan->consumed_token[i]) return 0;
+    if (plan->issued_token - tok >= kTokenRing) {
+        if (stale_out) *stale_out = true;
+        return 1;
+    }
+    return plan->seq_ring[tok % kTokenRing];
 }
 
-void static_consume(rdev_plan_t *plan, uint32_t i) {
+void static_consume(rdev_plan_t *plan, uint32_t i, uint32_t tok) {
     __atomic_store_n(&plan->h_flags[2 * i], 0u, __ATOMIC_RELEASE);
-    plan->consumed_token[i] = __atomic_load_n(plan->h_batch + plan->group_of[i], __ATOMIC_ACQUIRE);
+    plan->consumed_token[i] = tok;
 }
 
 uint32_t next_token(rdev_plan_t *plan, uint32_t seq) {
     if (++plan->issued_token == 0) ++plan->issued_token;      // 0 means "nothing delivered yet"
-    plan->seq_ring[plan->issued_token & 15] = seq;
+    plan->seq_ring[plan->issued_token % kTokenRing] = seq;
     return plan->issued_token;
+}
+
+rdev_status stale_error() {
+    return fail(RDEV_E_STATE, "more than " + std::to_string(kTokenRing - 1) + " whole-plan deliveries were issued behind the "
+                              "completed one: its flag value is no longer known (consume, or wait, more often)");
 }
 
 rdev_status launch_check(const char *what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(RDEV_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+    return RDEV_OK;
+}
+
+// A delivery on stream s is about to be enqueued.  If the receiver's last clear of this plan's flags travelled on
+// another stream and may still be pending, s waits for it: a late clear must not wipe the flags of this delivery.
+rdev_status before_delivery(rdev_plan_t *plan, hipStream_t s) {
+    if (plan->clear_pending && plan->clear_stream != s) {
+        const hipError_t q = hipEventQuery(plan->ev_clear);
+        if (q == hipErrorNotReady) {
+            (void)hipGetLastError();
+            HIP_TRY(hipStreamWaitEvent(s, plan->ev_clear, 0));
+        } else if (q != hipSuccess) {
+            return fail(RDEV_E_HIP, std::string("hipEventQuery: ") + hipGetErrorString(q));
+        }
+    }
+    plan->clear_pending = false;
+    plan->delivery_stream = s;
+    return RDEV_OK;
+}
+
+// A clear of in-arena flag words has just been enqueued on stream s.  The host-visible word that made the receiver
+// consume is stored after the in-arena words it stands for, so the clear needs no wait of its own; the next
+// delivery does (before_delivery) when s is not the stream it travels on.
+rdev_status after_clear(rdev_plan_t *plan, hipStream_t s) {
+    if (s == plan->delivery_stream) return RDEV_OK;
+    HIP_TRY(hipEventRecord(plan->ev_clear, s));
+    plan->clear_pending = true;
+    plan->clear_stream = s;
     return RDEV_OK;
 }
 
@@ -252,7 +313,7 @@ rdev_status launch_copy_table(const Item *items, const Item *subs, uint32_t n_bl
 rdev_status launch_group_flags(rdev_plan_t *plan, uint32_t g, uint32_t seq, uint32_t token, hipStream_t s) {
     const rdev_plan_s::Group &gr = plan->groups[g];
     if (!gr.n_flags) return RDEV_OK;
-    hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((gr.n_flags + 255) / 256), dim3(256), 0, s,
+    hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(1), dim3(rdev::kFlagTableThreads), 0, s,
                        plan->d_flags.ptr + gr.first_flag, gr.n_flags, seq, plan->d_batch_view + g, token);
     return launch_check("flag_table_kernel");
 }
@@ -373,7 +434,7 @@ rdev_status launch_inline_flags(rdev_plan_t *plan, const std::vector<std::pair<u
     while (i < v.size()) {
         rdev::InlineFlags f{};
         f.value = value;
-        while (i < v.size() && f.n < rdev::kInlineMax) {
+        while (i < v.size() && f.n < rdev::kFlagInlineMax) {
             f.arena_flag[f.n] = v[i].first;
             f.mirror_idx[f.n] = v[i].second;
             f.n++;
@@ -403,6 +464,7 @@ void drop_events(rdev_plan_t *plan) {
 void destroy_plan(rdev_plan_t *plan) {
     free_plan_blocks(plan);
     drop_events(plan);
+    if (plan->ev_clear) (void)hipEventDestroy(plan->ev_clear);
     if (plan->h_flags) (void)hipHostFree(plan->h_flags);
     if (plan->h_meta) (void)hipHostFree(plan->h_meta);
     plan->dev->n_plans--;
@@ -434,10 +496,17 @@ rdev_status rdev_open(rdev_device_t **out, int hip_device) {
         HIP_TRY(hipSetDevice(hip_device));
     }
     uint8_t *staging = nullptr;
-    if (hip_device >= 0) HIP_TRY(hipGetSymbolAddress((void **)&staging, HIP_SYMBOL(scratch)));   // this device's copy
+    rdev::ArenaEnt *d_arenas = nullptr;
+    if (hip_device >= 0) {
+        HIP_TRY(hipGetSymbolAddress((void **)&staging, HIP_SYMBOL(scratch)));   // this device's copy
+        HIP_TRY(hipMalloc((void **)&d_arenas, kMaxArenas * sizeof(rdev::ArenaEnt)));
+        hipError_t e = hipMemset(d_arenas, 0, kMaxArenas * sizeof(rdev::ArenaEnt));
+        if (e != hipSuccess) { (void)hipFree(d_arenas); return fail(RDEV_E_HIP, std::string("hipMemset: ") + hipGetErrorString(e)); }
+    }
     rdev_device_t *d = new rdev_device_t();
     d->hip_device = hip_device;
     d->fixed_staging = staging;
+    d->d_arenas = d_arenas;
     *out = d;
     return RDEV_OK;
 }
@@ -445,6 +514,7 @@ rdev_status rdev_open(rdev_device_t **out, int hip_device) {
 rdev_status rdev_close(rdev_device_t *dev) {
     if (!dev) return fail(RDEV_E_INVAL, "dev is NULL");
     if (dev->n_plans) return fail(RDEV_E_BUSY, "plans are still alive on this device");
+    if (dev->d_arenas) (void)hipFree(dev->d_arenas);
     delete dev;
     return RDEV_OK;
 }
@@ -462,6 +532,12 @@ rdev_status rdev_register_arena(rdev_device_t *dev, void *base, uint64_t bytes, 
         const uintptr_t lo = (uintptr_t)a.base, hi = lo + a.bytes, l2 = (uintptr_t)base, h2 = l2 + bytes;
         if (l2 < hi && lo < h2) return fail(RDEV_E_OVERLAP, "arena overlaps a registered arena");
     }
+    if (dev->arenas.size() >= kMaxArenas) return fail(RDEV_E_NOMEM, "a device registers at most " + std::to_string(kMaxArenas) + " arenas over its lifetime");
+    if (dev->gpu()) {      // the device-side copy used by receives that read the sender's address on the GPU
+        const rdev::ArenaEnt ent{(uint8_t *)base, bytes};
+        HIP_TRY(hipSetDevice(dev->hip_device));
+        HIP_TRY(hipMemcpy(dev->d_arenas + dev->arenas.size(), &ent, sizeof(ent), hipMemcpyHostToDevice));
+    }
     Arena a;
     a.base = (uint8_t *)base;
     a.bytes = bytes;
@@ -477,6 +553,11 @@ rdev_status rdev_unregister_arena(rdev_device_t *dev, uint32_t arena_id) {
     Arena *a;
     RDEV_TRY(arena_of(dev, arena_id, &a));
     if (a->alloc.live()) return fail(RDEV_E_BUSY, "regions are still allocated in arena " + std::to_string(arena_id));
+    if (dev->gpu()) {
+        const rdev::ArenaEnt none{nullptr, 0};
+        HIP_TRY(hipSetDevice(dev->hip_device));
+        HIP_TRY(hipMemcpy(dev->d_arenas + arena_id, &none, sizeof(none), hipMemcpyHostToDevice));
+    }
     *a = Arena();
     return RDEV_OK;
 }
@@ -588,7 +669,7 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
         };
         hipError_t e = hipSetDevice(dev->hip_device);
         if (e != hipSuccess) return bail(e, "hipSetDevice");
-        const size_t nflags = 2 * (size_t)n + 2 + o.flag_groups;
+        const size_t nflags = 2 * (size_t)n + o.flag_groups + 8;     // per-tensor pairs, group tokens, receive status
         e = hipHostMalloc((void **)&raw->h_flags, nflags * sizeof(uint32_t), hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { raw->h_flags = nullptr; return bail(e, "hipHostMalloc(flags)"); }
         std::memset(raw->h_flags, 0, nflags * sizeof(uint32_t));
@@ -596,6 +677,16 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
         if (e != hipSuccess) return bail(e, "hipHostGetDevicePointer(flags)");
         raw->h_batch = raw->h_flags + 2 * (size_t)n;
         raw->d_batch_view = raw->d_flags_view + 2 * (size_t)n;
+        raw->h_status = raw->h_batch + o.flag_groups;
+        raw->d_status_view = raw->d_batch_view + o.flag_groups;
+        e = hipEventCreateWithFlags(&raw->ev_clear, hipEventDisableTiming);
+        if (e != hipSuccess) { raw->ev_clear = nullptr; return bail(e, "hipEventCreate"); }
+        {
+            uint32_t w = 0;
+            for (auto &kv : raw->arenas) raw->heap_word_of[kv.first] = w++;
+            e = raw->d_heap.upload(std::vector<rdev::HeapWord>(std::max<size_t>(w, 1), rdev::HeapWord{0, 0, 0}));
+            if (e != hipSuccess) return bail(e, "upload(heap words)");
+        }
         raw->consumed_token.assign(n, 0);
         const size_t nmeta = std::max<size_t>(raw->n_dyn, 1);
         e = hipHostMalloc((void **)&raw->h_meta, nmeta * sizeof(rdev_meta), hipHostMallocMapped | hipHostMallocCoherent);
@@ -618,7 +709,7 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
         e = raw->d_flags.upload(fe);
         if (e != hipSuccess) return bail(e, "upload(flag table)");
         if (!fe.empty()) {
-            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(((uint32_t)fe.size() + 255) / 256), dim3(256), 0, 0,
+            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(1), dim3(rdev::kFlagTableThreads), 0, 0,
                                raw->d_flags.ptr, (uint32_t)fe.size(), 0u, (uint32_t *)nullptr, 0u);
             e = hipGetLastError();
             if (e != hipSuccess) return bail(e, "flag_table_kernel");
@@ -849,8 +940,13 @@ rdev_status check_busy_all(rdev_plan_t *plan) {
 rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipStream_t s) {
     if (!plan->copy_tables) RDEV_TRY(build_copy_tables(plan));
     RDEV_TRY(check_busy_all(plan));
+    if (mode != RDEV_SENDERCOPY && plan->heap_on_device)
+        return fail(RDEV_E_STATE, "this iteration's heap allocations were made on the device: call rdev_dyn_reset first");
+    RDEV_TRY(before_delivery(plan, s));
+    uint32_t token = 0;
     if (mode == RDEV_SENDERCOPY) {
         if (plan->stage_end > plan->send_buf.bytes) return fail(RDEV_E_NOMEM, "staging buffer too small");
+        if (plan->n_static) token = next_token(plan, seq);
         std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
         if (plan->n_stage_blocks) {
             RDEV_TRY(launch_copy_table(plan->d_stage_items.ptr, plan->d_stage_subs.ptr, plan->n_stage_blocks, s,
@@ -859,7 +955,6 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
                                        "copy_table_kernel(write)"));
         }
         if (plan->n_static) {
-            const uint32_t token = next_token(plan, seq);
             for (uint32_t g = 0; g < plan->groups.size(); ++g) RDEV_TRY(launch_group_flags(plan, g, seq, token, s));
         }
         return RDEV_OK;
@@ -878,6 +973,7 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
         hb.base[k] = arena_ptr(plan, plan->heap_slot_arena[k], al.heap_offset + al.heap_ptr);
     }
     if (plan->n_static) {
+        token = next_token(plan, seq);
         // pack: headers, then payloads
         hipLaunchKernelGGL(rdev::rpc_header_kernel, dim3((plan->n_static * 32 + 255) / 256), dim3(256), 0, s,
                            plan->d_headers.ptr, plan->d_msg_send.ptr, plan->n_static, seq,
@@ -906,11 +1002,10 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
                                (uint32_t)plan->opts.chunk_bytes);
             RDEV_TRY(launch_check("unpack_table_kernel"));
         }
-        const uint32_t token = next_token(plan, seq);
         for (uint32_t g = 0; g < plan->groups.size(); ++g) {
             const rdev_plan_s::Group &gr = plan->groups[g];
             if (!gr.n_flags) continue;
-            hipLaunchKernelGGL(rdev::rpc_flag_kernel, dim3((gr.n_flags + 255) / 256), dim3(256), 0, s,
+            hipLaunchKernelGGL(rdev::rpc_flag_kernel, dim3(1), dim3(rdev::kFlagTableThreads), 0, s,
                                plan->d_flags.ptr + gr.first_flag,
                                (wire ? plan->d_msg_recv.ptr : plan->d_msg_send.ptr) + gr.first_flag, gr.n_flags,
                                plan->d_batch_view + g, token);
@@ -951,6 +1046,8 @@ rdev_status rdev_plan_bind_buffers(rdev_plan_t *plan, const rdev_region *send_bu
 rdev_status rdev_dyn_reset(rdev_plan_t *plan) {
     if (!plan) return fail(RDEV_E_INVAL, "NULL argument");
     for (auto &kv : plan->arenas) kv.second.heap_ptr = 0;
+    plan->heap_epoch++;                 // the device-resident pointers of the last iteration no longer count
+    plan->heap_on_device = false;
     return RDEV_OK;
 }
 
@@ -968,7 +1065,9 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
     if (!plan->bound_all) return fail(RDEV_E_STATE, "not every static tensor has a bound source");
     std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
     RDEV_TRY(check_busy_all(plan));
-    const uint32_t token = plan->n_static ? next_token(plan, seq) : 0;
+    RDEV_TRY(before_delivery(plan, s));
+    uint32_t token = 0;
+    if (plan->n_static) token = next_token(plan, seq);
     for (uint32_t g = 0; g < plan->groups.size(); ++g) {
         const rdev_plan_s::Group &gr = plan->groups[g];
         if (gr.n_blocks) {
@@ -988,6 +1087,7 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
 static rdev_status write_dma_mode(rdev_plan_t *plan, uint32_t seq, hipStream_t s) {
     if (!plan->bound_all) return fail(RDEV_E_STATE, "not every static tensor has a bound source");
     RDEV_TRY(check_busy_all(plan));
+    RDEV_TRY(before_delivery(plan, s));
     std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
     for (uint32_t i = 0; i < plan->pl.size(); ++i) {
         const rdev_placement &p = plan->pl[i];
@@ -1015,6 +1115,8 @@ static rdev_status transfer_static_list(rdev_plan_t *plan, const std::vector<std
             return fail(RDEV_E_BUSY, "tensor " + std::to_string(p.tensor_id) + " has not been consumed");
         flags.emplace_back((uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset), 2 * list[k].first);
     }
+    RDEV_TRY(before_delivery(plan, s));
+    for (const auto &e : list) plan->rpc_valid[e.first] = 0;      // back in its static region
     RDEV_TRY(launch_inline_copies(plan, v, s));
     return launch_inline_flags(plan, flags, seq, true, s);
 }
@@ -1106,6 +1208,7 @@ rdev_status rdev_write_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_x
                     mb.n++;
                     ++k;
                 }
+                RDEV_TRY(before_delivery(plan, s));
                 hipLaunchKernelGGL(rdev::meta_write_kernel, dim3(mb.n), dim3(64), 0, s, mb, plan->d_flags_view,
                                    plan->d_meta_view);
                 RDEV_TRY(launch_check("meta_write_kernel"));
@@ -1155,6 +1258,7 @@ rdev_status rdev_write_batch_fixed_staging(rdev_device_t *dev, rdev_plan_t *plan
         ptr += (r.bytes + A - 1) & ~(A - 1);
     }
     for (const auto &e : list) plan->rpc_valid[e.first] = 0;
+    RDEV_TRY(before_delivery(plan, s));
     RDEV_TRY(launch_inline_copies(plan, stage, s));      // sender: tensor -> staging
     RDEV_TRY(launch_inline_copies(plan, write, s));      // staging -> receiver region (the kernel boundary orders the two)
     return launch_inline_flags(plan, flags, seq, true, s);
@@ -1187,6 +1291,8 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
             continue;
         }
         const int32_t di = plan->dyn_index[idx];
+        if (plan->heap_on_device)
+            return fail(RDEV_E_STATE, "this iteration's heap allocations were made on the device: call rdev_dyn_reset first");
         if (!plan->polled_valid[di]) return fail(RDEV_E_STATE, "metadata of tensor " + std::to_string(p.tensor_id) + " has not been polled");
         const rdev_meta &m = plan->polled[di];
         Arena *sa;
@@ -1242,6 +1348,72 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
     return RDEV_OK;
 }
 
+rdev_status rdev_read_batch_device(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n, uint32_t seq,
+                                   void *stream) {
+    if (!dev || !plan || plan->dev != dev || !x || !n) return fail(RDEV_E_INVAL, "NULL argument, empty batch or plan of another device");
+    if (!seq) return fail(RDEV_E_INVAL, "seq must be >= 1");
+    RDEV_TRY(require_gpu(dev));
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<uint32_t> idx(n);
+    for (uint32_t k = 0; k < n; ++k) {
+        RDEV_TRY(index_of(plan, x[k].tensor_id, &idx[k]));
+        if (plan->pl[idx[k]].kind != RDEV_DYNAMIC) return fail(RDEV_E_INVAL, "the device-side receive takes dynamic tensors");
+        for (uint32_t j = 0; j < k; ++j)
+            if (idx[j] == idx[k]) return fail(RDEV_E_INVAL, "a tensor is listed twice");
+    }
+    if (n > rdev::kRecvMax) return fail(RDEV_E_INVAL, "the device-side receive takes at most 8 tensors per call");
+    for (uint32_t first = 0; first < n; first += rdev::kRecvMax) {
+        rdev::RecvBatch b{};
+        b.n = std::min<uint32_t>(rdev::kRecvMax, n - first);
+        b.seq = seq;
+        b.epoch = plan->heap_epoch;
+        b.chunk = (uint32_t)plan->opts.chunk_bytes;
+        b.align = plan->opts.align;
+        b.n_arenas = (uint32_t)dev->arenas.size();
+        b.call_id = ++plan->recv_calls;
+        uint64_t room = 0;
+        for (uint32_t k = 0; k < b.n; ++k) {
+            const uint32_t i = idx[first + k];
+            const rdev_placement &p = plan->pl[i];
+            const ArenaLayout &al = plan->arenas[p.dst_arena];
+            rdev::RecvEnt &e = b.e[k];
+            e.slot = arena_ptr(plan, p.dst_arena, p.meta_offset);
+            e.arena_base = dev->arenas[p.dst_arena].base;
+            e.heap_offset = al.heap_offset;
+            e.heap_bytes = al.heap_bytes;
+            e.heap_ptr_host = al.heap_ptr;
+            e.heap_word = plan->heap_word_of[p.dst_arena];
+            e.dst_arena = p.dst_arena;
+            e.meta_idx = (uint32_t)plan->dyn_index[i];
+            e.flag_idx = 2 * i;
+            room += al.heap_bytes;
+            plan->polled_valid[plan->dyn_index[i]] = 0;
+        }
+        // the payload sizes are not known here: enough workgroups for what the heaps could take, within a bound
+        const uint64_t want = room / plan->opts.chunk_bytes + 1;
+        const uint32_t grid = (uint32_t)std::min<uint64_t>(want, rdev::kRecvMaxBlocks);
+        hipLaunchKernelGGL(rdev::recv_pull_kernel, dim3(grid), dim3(rdev::kBlockThreads), 0, s, b, dev->d_arenas, plan->d_heap.ptr);
+        RDEV_TRY(launch_check("recv_pull_kernel"));
+        hipLaunchKernelGGL(rdev::recv_post_kernel, dim3(1), dim3(64), 0, s, b, dev->d_arenas, plan->d_heap.ptr,
+                           plan->d_flags_view, plan->d_meta_view, plan->d_status_view);
+        RDEV_TRY(launch_check("recv_post_kernel"));
+        plan->heap_on_device = true;
+    }
+    return RDEV_OK;
+}
+
+rdev_status rdev_recv_status(rdev_plan_t *plan, int32_t *status_out, uint32_t *entry_out, uint32_t *calls_done_out,
+                             uint32_t *calls_made_out) {
+    if (!plan) return fail(RDEV_E_INVAL, "NULL argument");
+    RDEV_TRY(require_gpu(plan->dev));
+    const uint32_t done = __atomic_load_n(&plan->h_status[2], __ATOMIC_ACQUIRE);
+    if (calls_done_out) *calls_done_out = done;
+    if (status_out) *status_out = (int32_t)plan->h_status[0];
+    if (entry_out) *entry_out = plan->h_status[1];
+    if (calls_made_out) *calls_made_out = plan->recv_calls;
+    return RDEV_OK;
+}
+
 rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id, uint32_t poll_flags, rdev_meta *meta_out,
                       void *stream) {
     if (!dev || !plan || plan->dev != dev) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
@@ -1252,14 +1424,19 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
 
     if (tensor_id == RDEV_ALL_TENSORS) {
         if (poll_flags & (RDEV_POLL_META | RDEV_POLL_ARENA)) return fail(RDEV_E_INVAL, "RDEV_ALL_TENSORS polls host-visible static flags only");
+        std::vector<uint32_t> &toks = plan->tok_scratch;
+        toks.resize(plan->pl.size());
+        bool stale = false;
         for (uint32_t i = 0; i < plan->pl.size(); ++i)
-            if (plan->pl[i].kind == RDEV_STATIC && !static_ready(plan, i)) return RDEV_NOT_READY;
+            if (plan->pl[i].kind == RDEV_STATIC && !static_ready(plan, i, &toks[i], &stale)) return RDEV_NOT_READY;
+        if (stale) return stale_error();
         if (consume && plan->n_static) {
             for (uint32_t i = 0; i < plan->pl.size(); ++i)
-                if (plan->pl[i].kind == RDEV_STATIC) static_consume(plan, i);
-            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3((plan->n_static + 255) / 256), dim3(256), 0, s,
+                if (plan->pl[i].kind == RDEV_STATIC) static_consume(plan, i, toks[i]);
+            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(1), dim3(rdev::kFlagTableThreads), 0, s,
                                plan->d_flags.ptr, plan->n_static, 0u, (uint32_t *)nullptr, 0u);
             RDEV_TRY(launch_check("flag_table_kernel"));
+            RDEV_TRY(after_clear(plan, s));
         }
         return RDEV_OK;
     }
@@ -1273,11 +1450,14 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
     const uint32_t widx = 2 * idx + (want_meta ? 1 : 0);
     uint32_t *arena_flag = (uint32_t *)arena_ptr(plan, p.dst_arena, dyn ? p.meta_offset + (want_meta ? 124 : 120) : p.flag_offset);
 
-    uint32_t v;
+    uint32_t v, tok = 0;
+    if (!dyn) tok = __atomic_load_n(plan->h_batch + plan->group_of[idx], __ATOMIC_ACQUIRE);
     if (poll_flags & RDEV_POLL_ARENA) {
         HIP_TRY(hipMemcpy(&v, arena_flag, sizeof(v), hipMemcpyDeviceToHost));
     } else {
-        v = dyn ? __atomic_load_n(&plan->h_flags[widx], __ATOMIC_ACQUIRE) : static_ready(plan, idx);
+        bool stale = false;
+        v = dyn ? __atomic_load_n(&plan->h_flags[widx], __ATOMIC_ACQUIRE) : static_ready(plan, idx, &tok, &stale);
+        if (stale) return stale_error();
     }
     if (!v) return RDEV_NOT_READY;
 
@@ -1309,9 +1489,10 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
     }
     if (consume) {
         if (dyn) __atomic_store_n(&plan->h_flags[widx], 0u, __ATOMIC_RELEASE);
-        else static_consume(plan, idx);
+        else static_consume(plan, idx, tok);
         std::vector<std::pair<uint32_t *, uint32_t>> f{{arena_flag, widx}};
         RDEV_TRY(launch_inline_flags(plan, f, 0u, false, s));
+        RDEV_TRY(after_clear(plan, s));
     }
     return RDEV_OK;
 }
@@ -1342,7 +1523,7 @@ rdev_status rdev_gather_unique_rows(rdev_device_t *dev, const int64_t *ids, uint
 static rdev_status consume_checked(rdev_plan_t *plan, uint32_t idx, uint32_t max_spins, rdev_consume_result *out,
                                    hipStream_t s) {
     const rdev_placement &p = plan->pl[idx];
-    hipLaunchKernelGGL(rdev::consume_init_kernel, dim3(1), dim3(64), 0, s, out);
+    hipLaunchKernelGGL(rdev::consume_init_kernel, dim3(1), dim3(64), 0, s, out, 1u);
     RDEV_TRY(launch_check("consume_init_kernel"));
     const uint64_t per_block = (uint64_t)rdev::kConsumeThreads * 16 * 16;        // 64 KiB of payload per workgroup pass
     const uint32_t cap = max_spins ? rdev::kConsumeMaxBlocks : rdev::kConsumeMaxBlocksNoWait;
@@ -1372,6 +1553,45 @@ rdev_status rdev_consume_reduce_max(rdev_device_t *dev, rdev_plan_t *plan, uint3
     return consume_checked(plan, idx, max_spins, out, (hipStream_t)stream);
 }
 
+// one launch (per 32 tensors) over a list of validated static tensors; out[k] belongs to idx[k]
+static rdev_status consume_list(rdev_plan_t *plan, const uint32_t *idx, uint32_t n, uint32_t max_spins,
+                                rdev_consume_result *out, hipStream_t s) {
+    if (!n) return RDEV_OK;
+    hipLaunchKernelGGL(rdev::consume_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, out, n);
+    RDEV_TRY(launch_check("consume_init_kernel"));
+    for (uint32_t first = 0; first < n; first += rdev::kConsumeBatchMax) {
+        rdev::ConsumeBatch b{};
+        b.n = std::min<uint32_t>(rdev::kConsumeBatchMax, n - first);
+        b.max_spins = max_spins;
+        uint64_t units = 0;
+        for (uint32_t k = 0; k < b.n; ++k) {
+            const rdev_placement &p = plan->pl[idx[first + k]];
+            const uint64_t nvec = p.bytes >> 4, per = rdev::kConsumeUnitBytes / 16;
+            const uint64_t nu = std::max<uint64_t>(1, (nvec + per - 1) / per);
+            if (units + nu > 0xFFFFFFFFull) return fail(RDEV_E_INVAL, "tensor list too large for one consumer batch");
+            b.e[k] = rdev::ConsumeEnt{(const uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset),
+                                      (const uint8_t *)arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, (uint32_t)units,
+                                      (uint32_t)nu};
+            units += nu;
+        }
+        b.n_units = (uint32_t)units;
+        const uint32_t cap = max_spins ? rdev::kConsumeTableMaxBlocks : rdev::kConsumeMaxBlocksNoWait;
+        hipLaunchKernelGGL(rdev::consume_table_kernel, dim3(std::min<uint32_t>(b.n_units, cap)), dim3(rdev::kConsumeThreads), 0, s,
+                           b, out + first);
+        RDEV_TRY(launch_check("consume_table_kernel"));
+    }
+    return RDEV_OK;
+}
+
+rdev_status rdev_consume_batch(rdev_device_t *dev, rdev_plan_t *plan, const uint32_t *tensor_ids, uint32_t n,
+                               uint32_t max_spins, rdev_consume_result *out, void *stream) {
+    if (!dev || !plan || plan->dev != dev || (!tensor_ids && n)) return fail(RDEV_E_INVAL, "NULL argument or plan of another device");
+    RDEV_TRY(require_gpu(dev));
+    std::vector<uint32_t> idx(n);
+    for (uint32_t i = 0; i < n; ++i) RDEV_TRY(consume_validate(plan, tensor_ids[i], out + i, &idx[i]));
+    return consume_list(plan, idx.data(), n, max_spins, out, (hipStream_t)stream);
+}
+
 rdev_status rdev_recv_polling_async(rdev_device_t *dev, rdev_plan_t *plan, const uint32_t *tensor_ids, uint32_t n,
                                     rdev_consume_result *out, void *flag_stream, void *consumer_stream,
                                     uint64_t max_polls, uint64_t *polls_out) {
@@ -1384,10 +1604,34 @@ rdev_status rdev_recv_polling_async(rdev_device_t *dev, rdev_plan_t *plan, const
     size_t head = 0;
     uint64_t polls = 0, failed = 0;
     rdev_status result = RDEV_OK;
+    // Ops whose poll succeeded since the last failed poll turn asynchronous together: one clear launch and one
+    // consumer launch for the run, instead of two launches per tensor.  Results must be contiguous per launch, so a
+    // run is cut where the caller's positions stop being consecutive.
+    std::vector<uint32_t> run;                      // positions, consecutive and ascending
+    auto flush = [&]() -> rdev_status {
+        if (run.empty()) return RDEV_OK;
+        std::vector<std::pair<uint32_t *, uint32_t>> f;
+        std::vector<uint32_t> ridx;
+        for (uint32_t pos : run) {
+            const rdev_placement &p = plan->pl[idx[pos]];
+            f.emplace_back((uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset), 2 * idx[pos]);
+            ridx.push_back(idx[pos]);
+        }
+        RDEV_TRY(launch_inline_flags(plan, f, 0u, false, (hipStream_t)flag_stream));
+        RDEV_TRY(after_clear(plan, (hipStream_t)flag_stream));
+        RDEV_TRY(consume_list(plan, ridx.data(), (uint32_t)ridx.size(), 0, out + run.front(), (hipStream_t)consumer_stream));
+        run.clear();
+        return RDEV_OK;
+    };
     while (head < queue.size()) {
         const uint32_t i = queue[head++];
         ++polls;
-        if (!static_ready(plan, idx[i])) {
+        uint32_t tok;
+        bool stale = false;
+        const uint32_t ready = static_ready(plan, idx[i], &tok, &stale);
+        if (stale) return stale_error();
+        if (!ready) {
+            RDEV_TRY(flush());                      // what is ready starts before the host goes on waiting
             if (++failed >= max_polls) { result = RDEV_NOT_READY; break; }
             queue.push_back(i);                     // back to the tail of the ready queue
             if (head > 4096 && head * 2 > queue.size()) {   // keep the vector from growing without bound
@@ -1397,12 +1641,11 @@ rdev_status rdev_recv_polling_async(rdev_device_t *dev, rdev_plan_t *plan, const
             continue;
         }
         // success: consume the flag, the op turns asynchronous
-        static_consume(plan, idx[i]);
-        const rdev_placement &p = plan->pl[idx[i]];
-        std::vector<std::pair<uint32_t *, uint32_t>> f{{(uint32_t *)arena_ptr(plan, p.dst_arena, p.flag_offset), 2 * idx[i]}};
-        RDEV_TRY(launch_inline_flags(plan, f, 0u, false, (hipStream_t)flag_stream));
-        RDEV_TRY(consume_checked(plan, idx[i], 0, out + i, (hipStream_t)consumer_stream));
+        static_consume(plan, idx[i], tok);
+        if (!run.empty() && (i != run.back() + 1 || run.size() == rdev::kConsumeBatchMax)) RDEV_TRY(flush());
+        run.push_back(i);
     }
+    RDEV_TRY(flush());
     if (polls_out) *polls_out = polls;
     return result;
 }

@@ -100,6 +100,10 @@ SYMBOLS = {
     "rdev_write_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, C.c_uint32, _P]),
     "rdev_write_batch_fixed_staging": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
     "rdev_read_batch": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
+    "rdev_read_batch_device": (C.c_int32, [_P, _P, C.POINTER(Xfer), C.c_uint32, C.c_uint32, _P]),
+    "rdev_recv_status": (C.c_int32, [_P, C.POINTER(C.c_int32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                     C.POINTER(C.c_uint32)]),
+    "rdev_consume_batch": (C.c_int32, [_P, _P, C.POINTER(C.c_uint32), C.c_uint32, C.c_uint32, _P, _P]),
     "rdev_poll": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, C.POINTER(Meta), _P]),
     "rdev_gather_unique_rows": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P, _P, _P, _P]),
     "rdev_consume_reduce_max": (C.c_int32, [_P, _P, C.c_uint32, C.c_uint32, _P, _P]),
@@ -279,6 +283,22 @@ def rdev_write_batch_fixed_staging(dev: int, plan: int, x: Optional[Sequence[Xfe
 def rdev_read_batch(dev: int, plan: int, x: Optional[Sequence[Xfer]] = None, seq: int = 1, stream: int = 0) -> None:
     arr, n = _xfers(x)
     _check(lib().rdev_read_batch(dev, plan, arr, n, seq, stream or None))
+
+
+def rdev_read_batch_device(dev: int, plan: int, x: Sequence[Xfer], seq: int = 1, stream: int = 0) -> None:
+    arr, n = _xfers(x)
+    _check(lib().rdev_read_batch_device(dev, plan, arr, n, seq, stream or None))
+
+
+def rdev_recv_status(plan: int) -> dict:
+    st, ent, done, made = C.c_int32(), C.c_uint32(), C.c_uint32(), C.c_uint32()
+    _check(lib().rdev_recv_status(plan, C.byref(st), C.byref(ent), C.byref(done), C.byref(made)))
+    return dict(status=st.value, entry=ent.value, calls_done=done.value, calls_made=made.value)
+
+
+def rdev_consume_batch(dev: int, plan: int, tensor_ids: Sequence[int], max_spins: int, out_ptr: int, stream: int = 0) -> None:
+    arr = (C.c_uint32 * max(len(tensor_ids), 1))(*tensor_ids)
+    _check(lib().rdev_consume_batch(dev, plan, arr, len(tensor_ids), max_spins, out_ptr, stream or None))
 
 
 def rdev_poll(dev: int, plan: int, tensor_id: int = ALL_TENSORS, poll_flags: int = 0, stream: int = 0,

@@ -165,6 +165,67 @@ def test_consumer_and_polling_async_on_gpu():
     g.close()
 
 
+def _check_results(got, o, ids, seen):
+    for k, t in enumerate(ids):
+        mx, ws = O.consume_reduce_max(o.dev, o.plan, t)
+        assert got[k] == (0, seen, _bits(mx), ws), (k, t, got[k], hex(_bits(mx)), ws)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,groups", [("mixed", 1), ("mixed", 3), ("vgg16", 4)])
+def test_consume_batch_one_launch_for_a_list(name, groups):
+    """rdev_consume_batch: (a) after the delivery, no waiting; (b) enqueued on a second stream right behind a
+    delivery that is still in flight, every unit waiting for its tensor's in-arena flag; (c) nothing delivered:
+    every workgroup gives up after its spins and leaves, status 1.  Results equal the checker's exactly."""
+    import torch
+    from gpu_harness import GpuRun
+    wl = W.vgg16() if name == "vgg16" else W.small_mixed(63, n=40, max_bytes=2_000_000, n_recv=3, dtypes=("f32",), gran=4)
+    g, o = GpuRun(wl, flag_groups=groups), OracleRun(wl)
+    ids = list(range(len(wl.tensors)))
+    n = len(ids)
+    res = torch.zeros(n * 24 + 16, dtype=torch.uint8, device="cuda:0")
+    base = (res.data_ptr() + 15) // 16 * 16
+    res_v = res[base - res.data_ptr():]
+    cons = torch.cuda.Stream()
+    # (c) first: nothing has been delivered yet
+    R.rdev_consume_batch(g.dev, g.plan, ids, 50, base, cons.cuda_stream)
+    cons.synchronize()
+    assert all(r[0] == 1 for r in _results(res_v, n))
+    # (a)
+    R.rdev_write_batch(g.dev, g.plan, None, R.ZEROCOPY, 3, g.s)
+    O.static_write(o.dev, o.plan, o.sources, 3)
+    g.stream.synchronize()
+    R.rdev_consume_batch(g.dev, g.plan, ids, 0, base, cons.cuda_stream)
+    cons.synchronize()
+    _check_results(_results(res_v, n), o, ids, 0)
+    # a shuffled sub-list
+    sub = [ids[k] for k in (5, 0, n - 1, 7, 2)]
+    R.rdev_consume_batch(g.dev, g.plan, sub, 0, base, cons.cuda_stream)
+    cons.synchronize()
+    _check_results(_results(res_v, len(sub)), o, sub, 0)
+    # (b) several rounds with fresh data: a flag seen before its payload would show as a stale checksum
+    for rnd in range(4):
+        assert R.rdev_poll(g.dev, g.plan, R.ALL_TENSORS, R.POLL_CONSUME, g.s)
+        for t in ids:
+            assert O.poll(o.dev, o.plan, t, consume=True)[0]
+        imgs = W.fill_sources(wl, variant=40 + rnd)
+        g.set_sources(imgs)
+        for sid, img in zip(o.send_ids, imgs):
+            o.image(sid)[:] = img
+        R.rdev_write_batch(g.dev, g.plan, None, R.ZEROCOPY, 10 + rnd, g.s)
+        R.rdev_consume_batch(g.dev, g.plan, ids, 2_000_000, base, cons.cuda_stream)
+        O.static_write(o.dev, o.plan, o.sources, 10 + rnd)
+        cons.synchronize()
+        _check_results(_results(res_v, n), o, ids, 10 + rnd)
+        g.stream.synchronize()
+    for aid in o.recv_ids:
+        assert np.array_equal(g.image(aid), o.image(aid))          # the consumer changes nothing in the arenas
+    with pytest.raises(R.RdevError) as e:
+        R.rdev_consume_batch(g.dev, g.plan, [0, 999], 0, base, cons.cuda_stream)
+    assert e.value.status == R.E_INVAL
+    g.close()
+
+
 @pytest.mark.gpu
 def test_consumer_special_values_on_gpu():
     import torch

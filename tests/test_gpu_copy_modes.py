@@ -109,6 +109,50 @@ def test_fragmented_rpc3_full_size(name):
     _run_modes(W.CONFIGS[name](), iters=1, frag=1 << 20, tight=True, modes=[(R.RPC3, O.MODE_RPC3), (R.RPC2, O.MODE_RPC2)])
 
 
+def test_poll_names_the_region_again_after_a_zero_copy_delivery():
+    """RPC delivery (fresh heap allocation, the poll says where), then a zero-copy delivery of some of the
+    tensors as an explicit batch and of all as a whole plan: the poll must name the static region again."""
+    from gpu_harness import GpuRun
+    wl = W.small_mixed(41, n=8, max_bytes=30000, n_recv=2, gran=4)
+    bufsz, heap = _sizes(wl)
+    g = GpuRun(wl, heap=heap, extra_arenas=(bufsz, bufsz))
+    o = OracleRun(wl, heap=heap, extra_arenas=(bufsz, bufsz))
+    gs = R.rdev_alloc_region(g.dev, g.extra_ids[0], bufsz - 256, 256)
+    os_ = o.dev.alloc_region(o.extra_ids[0], bufsz - 256, 256)
+    R.rdev_plan_bind_buffers(g.plan, gs, None)
+    ids = list(range(len(wl.tensors)))
+
+    def check_offsets():
+        for t in ids:
+            ok, m = R.rdev_poll(g.dev, g.plan, t, 0, g.s, want_meta=True)
+            ok2, m2 = O.poll(o.dev, o.plan, t)
+            assert ok == ok2
+            if ok:
+                assert m.dst_offset == (m2["dst_offset"] if m2 else o.plan.get(t).data_offset), t
+
+    R.rdev_write_batch(g.dev, g.plan, None, R.RPC2, 1, g.s)
+    O.copy_write(o.dev, o.plan, o.sources, O.MODE_RPC2, 1, os_)
+    assert g.wait_all()
+    check_offsets()
+    assert R.rdev_poll(g.dev, g.plan, R.ALL_TENSORS, R.POLL_CONSUME, g.s)
+    for t in ids:
+        O.poll(o.dev, o.plan, t, consume=True)
+    back = [1, 4, 6]
+    R.rdev_write_batch(g.dev, g.plan, [R.make_xfer(t) for t in back], R.ZEROCOPY, 2, g.s)
+    O.static_write(o.dev, o.plan, o.sources, 2, tensor_ids=back)
+    for t in back:
+        g.wait(t)
+    check_offsets()
+    for t in back:
+        assert R.rdev_poll(g.dev, g.plan, t, R.POLL_CONSUME, g.s) and O.poll(o.dev, o.plan, t, consume=True)[0]
+    R.rdev_write_batch(g.dev, g.plan, None, R.ZEROCOPY, 3, g.s)
+    O.static_write(o.dev, o.plan, o.sources, 3)
+    assert g.wait_all()
+    check_offsets()
+    _compare_all(g, o, "rpc, then explicit zero-copy, then whole-plan zero-copy")
+    g.close()
+
+
 def test_copy_mode_errors():
     from gpu_harness import GpuRun
     wl = W.small_mixed(5, n=6, max_bytes=4000, n_recv=1)

@@ -19,12 +19,14 @@ def _meta_dict(m):
                 data_flag=m.data_flag, meta_flag=m.meta_flag)
 
 
-def _dynamic_round(g, o, it, sends, src_arena_idx, reset=True):
+def _dynamic_round(g, o, it, sends, src_arena_idx, reset=True, device_recv=False):
     """sends: list of (tensor_id, dtype name, dims, payload bytes).  Payloads are
     laid into extra arena `src_arena_idx` at 4-byte (not 16-byte) aligned offsets.
     An entry (tensor_id, dtype name, dims, None, (arena id, offset)) names a tensor
     that already sits in registered memory.  reset=False keeps the heaps as they
-    are (later tensors of the same iteration)."""
+    are (later tensors of the same iteration).  device_recv=True: the receiver's
+    half runs on the GPU behind the metadata write (rdev_read_batch_device), with
+    no host poll of the metadata; the checker goes through the same steps as ever."""
     if reset:
         R.rdev_dyn_reset(g.plan)
         O.dyn_reset(o.plan)
@@ -54,14 +56,29 @@ def _dynamic_round(g, o, it, sends, src_arena_idx, reset=True):
     for tid, dt, dims, so, sa in xs:
         O.dyn_send(o.dev, o.plan, tid, (sa, so), O.DTYPE_CODE[dt], dims, it)
     # receiver: poll metadata (consume), pull, poll payload flag (consume)
-    for tid, dt, dims, so, sa in xs:
-        assert not R.rdev_poll(g.dev, g.plan, tid)                               # payload flag not set yet
-        ok, m = g.wait(tid, R.POLL_META | R.POLL_CONSUME, want_meta=True)
-        ok2, m2 = O.poll(o.dev, o.plan, tid, consume=True, which=O.POLL_META)
-        assert ok and ok2 and _meta_dict(m) == m2
-        assert not R.rdev_poll(g.dev, g.plan, tid, R.POLL_META)
-    _compare_all(g, o, f"round {it}: metadata delivered and consumed")
-    R.rdev_read_batch(g.dev, g.plan, [R.make_xfer(tid) for tid, *_ in xs], it, g.s)
+    if device_recv:
+        made = R.rdev_recv_status(g.plan)["calls_made"]
+        for k in range(0, len(xs), 8):
+            R.rdev_read_batch_device(g.dev, g.plan, [R.make_xfer(tid) for tid, *_ in xs[k:k + 8]], it, g.s)
+        for tid, *_ in xs:
+            assert O.poll(o.dev, o.plan, tid, consume=True, which=O.POLL_META)[0]
+        g.stream.synchronize()
+        st = R.rdev_recv_status(g.plan)
+        assert st["status"] == R.OK and st["calls_done"] == st["calls_made"] == made + (len(xs) + 7) // 8
+        for tid, *_ in xs:
+            assert not R.rdev_poll(g.dev, g.plan, tid, R.POLL_META)              # consumed on the device
+        with pytest.raises(R.RdevError) as e:                                    # the heap pointers now live on the device
+            R.rdev_read_batch(g.dev, g.plan, [R.make_xfer(xs[0][0])], it, g.s)
+        assert e.value.status == R.E_STATE
+    else:
+        for tid, dt, dims, so, sa in xs:
+            assert not R.rdev_poll(g.dev, g.plan, tid)                               # payload flag not set yet
+            ok, m = g.wait(tid, R.POLL_META | R.POLL_CONSUME, want_meta=True)
+            ok2, m2 = O.poll(o.dev, o.plan, tid, consume=True, which=O.POLL_META)
+            assert ok and ok2 and _meta_dict(m) == m2
+            assert not R.rdev_poll(g.dev, g.plan, tid, R.POLL_META)
+        _compare_all(g, o, f"round {it}: metadata delivered and consumed")
+        R.rdev_read_batch(g.dev, g.plan, [R.make_xfer(tid) for tid, *_ in xs], it, g.s)
     dsts = [O.dyn_recv(o.dev, o.plan, tid, it) for tid, *_ in xs]
     for (tid, dt, dims, so, sa), dst in zip(xs, dsts):
         ok, m = g.wait(tid, 0, want_meta=True)
@@ -165,6 +182,109 @@ def test_dynamic_errors_and_heap_exhaustion():
     with pytest.raises(O.OracleError):
         O.dyn_recv(o.dev, o.plan, d1, 1)
     _compare_all(g, o, "after exhaustion")
+    g.close()
+
+
+def test_device_side_receive_tiny_and_lstm():
+    """The receiver's half on the GPU (no host poll between metadata and pull): same arena images, same
+    records, for the tiny config's two tensors over three iterations and for the sparse LSTM gradient."""
+    from gpu_harness import GpuRun
+    wl = W.tiny()
+    heap = 2 << 20
+    g = GpuRun(wl, heap=heap, extra_arenas=(2 << 20,))
+    o = OracleRun(wl, heap=heap, extra_arenas=(2 << 20,))
+    dyn = [i for i, t in enumerate(wl.tensors) if not t.is_static]
+    for it in range(1, 4):
+        rows = W.tiny_dynamic_rows(it)
+        sends = [(t, "f32", (r, 256), W.dynamic_payload(r * 1024, 100 * it + t)) for t, r in zip(dyn, rows)]
+        _dynamic_round(g, o, it, sends, 0, device_recv=True)
+    g.close()
+    wl = W.lstm()
+    table = W.lstm_embedding_table()
+    heap = 8 << 20
+    g = GpuRun(wl, heap=heap, extra_arenas=(8 << 20,))
+    o = OracleRun(wl, heap=heap, extra_arenas=(8 << 20,))
+    for it in range(1, 3):
+        u = np.unique(W.lstm_token_ids(it).reshape(-1))
+        sends = [(3, "i64", (u.size,), u.astype(np.int64).view(np.uint8).copy()),
+                 (4, "f32", (u.size, 1024), np.ascontiguousarray(table[u]).view(np.uint8).reshape(-1).copy())]
+        _dynamic_round(g, o, it, sends, 0, device_recv=(it == 1))      # iteration 2 through the host again
+    g.close()
+
+
+def test_device_side_receive_many_tensors_mixed_with_host_path():
+    """12 dynamic tensors over 3 arenas, odd sizes and element types: the first 4 received through the host path,
+    the rest on the device in the same iteration (one heap, allocation order = batch order throughout)."""
+    from gpu_harness import GpuRun
+    wl = W.small_mixed(71, n=6, max_bytes=3000, n_recv=3, n_dynamic=12)
+    heap = 1 << 20
+    g = GpuRun(wl, heap=heap, extra_arenas=(4 << 20,))
+    o = OracleRun(wl, heap=heap, extra_arenas=(4 << 20,))
+    dyn = [i for i, t in enumerate(wl.tensors) if not t.is_static]
+    rng = np.random.Generator(np.random.PCG64(5))
+    for it in range(1, 4):
+        sends = []
+        for t in dyn:
+            r = int(rng.integers(0, 9000))                              # rows of 8 fp32; 0 rows is legal
+            sends.append((t, "f32", (r, 8), W.dynamic_payload(r * 32, 1000 * it + t)))
+        _dynamic_round(g, o, it, sends[:4], 0)
+        # the later payloads must not overwrite the first four in the source arena: place them behind
+        _dynamic_round_at(g, o, it, sends[4:], 0, 2 << 20, device_recv=True)
+    g.close()
+
+
+def _dynamic_round_at(g, o, it, sends, src_arena_idx, base, **kw):
+    """_dynamic_round with the payloads laid out from byte `base` of the source arena, heaps kept."""
+    import torch as _t
+    pre = []
+    off = base
+    src_id = o.extra_ids[src_arena_idx]
+    for tid, dt, dims, payload in sends:
+        off = O.round_up(off, 16) + 4
+        o.image(src_id)[off:off + payload.size] = payload
+        g.extra_t[src_arena_idx][off:off + payload.size].copy_(_t.from_numpy(payload))
+        pre.append((tid, dt, dims, None, (src_id, off)))
+        off += payload.size
+    _t.cuda.synchronize()
+    _dynamic_round(g, o, it, pre, src_arena_idx, reset=False, **kw)
+
+
+def test_device_side_receive_refuses_a_batch_that_cannot_be_served():
+    from gpu_harness import GpuRun
+    wl = W.small_mixed(12, n=4, max_bytes=3000, n_recv=1, n_dynamic=2)
+    g = GpuRun(wl, heap=2048, extra_arenas=(1 << 16,))
+    o = OracleRun(wl, heap=2048, extra_arenas=(1 << 16,))
+    d0, d1 = 4, 5
+    src = g.extra_t[0].data_ptr()
+    # nothing sent yet: the metadata flag is not set
+    R.rdev_read_batch_device(g.dev, g.plan, [R.make_xfer(d0)], 1, g.s)
+    g.stream.synchronize()
+    st = R.rdev_recv_status(g.plan)
+    assert (st["status"], st["entry"], st["calls_done"]) == (R.NOT_READY, 0, 1)
+    _compare_all(g, o, "receive before the metadata arrived moves nothing")
+    # two tensors of 1280 B each (rounded to 1280): the 2048 B heap takes only the first -> the batch moves nothing
+    R.rdev_write_batch(g.dev, g.plan, [R.make_xfer(d0, src, R.F32, (40, 8)), R.make_xfer(d1, src + 4096, R.F32, (40, 8))],
+                       R.ZEROCOPY, 1, g.s)
+    O.dyn_send(o.dev, o.plan, d0, (o.extra_ids[0], 0), O.DTYPE_CODE["f32"], (40, 8), 1)
+    O.dyn_send(o.dev, o.plan, d1, (o.extra_ids[0], 4096), O.DTYPE_CODE["f32"], (40, 8), 1)
+    R.rdev_read_batch_device(g.dev, g.plan, [R.make_xfer(d0), R.make_xfer(d1)], 1, g.s)
+    g.stream.synchronize()
+    st = R.rdev_recv_status(g.plan)
+    assert (st["status"], st["entry"], st["calls_done"]) == (R.E_NOMEM, 1, 2)
+    _compare_all(g, o, "a batch that does not fit moves nothing, metadata flags stay set")
+    assert R.rdev_poll(g.dev, g.plan, d0, R.POLL_META) and R.rdev_poll(g.dev, g.plan, d1, R.POLL_META)
+    # the first alone fits
+    R.rdev_read_batch_device(g.dev, g.plan, [R.make_xfer(d0)], 1, g.s)
+    assert O.poll(o.dev, o.plan, d0, True, O.POLL_META)[0]
+    O.dyn_recv(o.dev, o.plan, d0, 1)
+    g.wait(d0)
+    assert R.rdev_recv_status(g.plan)["status"] == R.OK
+    _compare_all(g, o, "first tensor received on the device")
+    # argument checks
+    for xs in ([R.make_xfer(0)], [R.make_xfer(d0), R.make_xfer(d0)], [R.make_xfer(d0)] * 9, [R.make_xfer(99)]):
+        with pytest.raises(R.RdevError) as e:
+            R.rdev_read_batch_device(g.dev, g.plan, xs, 1, g.s)
+        assert e.value.status == R.E_INVAL
     g.close()
 
 

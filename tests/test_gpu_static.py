@@ -188,6 +188,57 @@ def test_one_batch_per_destination_on_its_own_stream(name):
     g.close()
 
 
+def test_receiver_clears_flags_on_its_own_stream():
+    """Deliveries on one stream, the receiver's consume (host poll + in-arena clear) on another, back to back for
+    many iterations with two plans in rotation: no flag may be lost to a late clear and none may survive a consume."""
+    from gpu_harness import GpuRun
+    wl = W.small_mixed(93, n=50, max_bytes=600000, n_recv=4, gran=1)
+    runs = [(GpuRun(wl), OracleRun(wl)) for _ in range(2)]
+    recv_streams = [torch.cuda.Stream() for _ in runs]
+    prev = None
+    for it in range(1, 25):
+        k = it % 2
+        g, o = runs[k]
+        R.rdev_write_batch(g.dev, g.plan, None, R.ZEROCOPY, it, g.s)
+        O.static_write(o.dev, o.plan, o.sources, it)
+        if prev is not None:
+            pg, po, ps = prev
+            assert pg.wait_all()
+            assert R.rdev_poll(pg.dev, pg.plan, R.ALL_TENSORS, R.POLL_CONSUME, ps.cuda_stream)
+            for t in range(len(wl.tensors)):
+                assert O.poll(po.dev, po.plan, t, consume=True)[0]
+        prev = (g, o, recv_streams[k])
+        if it % 6 == 0:             # look at everything now and then
+            pg, po, ps = prev
+            assert pg.wait_all()
+            for s_ in recv_streams:
+                s_.synchronize()
+            for gg, oo in runs:
+                _compare_all(gg, oo, f"iteration {it}")
+    # per-tensor consumes on the receiver's stream, explicit batches on the delivery stream
+    g, o = runs[0]
+    assert g.wait_all()
+    assert R.rdev_poll(g.dev, g.plan, R.ALL_TENSORS, R.POLL_CONSUME, recv_streams[0].cuda_stream)
+    for t in range(len(wl.tensors)):
+        assert O.poll(o.dev, o.plan, t, consume=True)[0]
+    for it in range(30, 40):
+        ids = [(7 * it + j) % len(wl.tensors) for j in range(5)]
+        ids = sorted(set(ids))
+        R.rdev_write_batch(g.dev, g.plan, [R.make_xfer(t) for t in ids], R.ZEROCOPY, it, g.s)
+        O.static_write(o.dev, o.plan, o.sources, it, tensor_ids=ids)
+        for t in ids:
+            g.wait(t)
+            assert R.rdev_poll(g.dev, g.plan, t, R.POLL_CONSUME, recv_streams[0].cuda_stream)
+            assert O.poll(o.dev, o.plan, t, consume=True)[0]
+    for s_ in recv_streams:
+        s_.synchronize()
+    for gg, oo in runs:
+        gg.stream.synchronize()
+    _compare_all(g, o, "per-tensor consumes on the receiver's stream")
+    for gg, _ in runs:
+        gg.close()
+
+
 def test_error_paths_on_gpu_device():
     from gpu_harness import GpuRun
     wl = W.small_mixed(3, n=6, max_bytes=5000, n_recv=1)
