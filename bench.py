@@ -70,8 +70,10 @@ def parse():
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a few plain device-to-device copies of known size (for counter calibration)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--time-every", type=int, default=8,
-                    help="bracket every n-th copy-kernel launch of a set with HIP events")
+    ap.add_argument("--time-every", type=int, default=1,
+                    help="time every n-th copy-kernel launch of a set with HIP events (the launch's own start/stop events)")
+    ap.add_argument("--host-dynamic", action="store_true",
+                    help="dynamic tensors: receive through the host (metadata poll, then rdev_read_batch) instead of on the device")
     return ap.parse_args()
 
 
@@ -279,10 +281,46 @@ def consumer_leg(R, torch, W, dev, wl, opts, s, spin, iters=20):
             tt.append((time.perf_counter() - t0) * 1e6)
         tg.close()
         grouped[f"flag_groups_{G}"] = round(sorted(tt[2:])[len(tt[2:]) // 2], 1)
+    # one batched write, then ONE consumer launch for the whole list: (a) after the host has seen the delivery,
+    # (b) enqueued right behind the write, every unit waiting on the device for its tensor's in-arena flag
+    one_launch = {}
+    for G in (1, 4, 8):
+        images = W.fill_sources(wl, 0)
+        tg = TransferSet(R, torch, W, dev, wl, images, dict(opts, flag_groups=G))
+        del images
+        for how in ("after_host_poll", "waiting_on_device"):
+            tt = []
+            for it in range(iters + 2):
+                torch.cuda.synchronize()
+                seq += 1
+                t0 = time.perf_counter()
+                R.rdev_write_batch(dev, tg.plan, None, R.ZEROCOPY, seq, s)
+                if how == "after_host_poll":
+                    spin(lambda: R.rdev_poll(dev, tg.plan, R.ALL_TENSORS))
+                    R.rdev_consume_batch(dev, tg.plan, ids, 0, base, c)
+                else:
+                    R.rdev_consume_batch(dev, tg.plan, ids, 4_000_000, base, c)
+                cons.synchronize()
+                torch.cuda.synchronize()
+                tt.append((time.perf_counter() - t0) * 1e6)
+                R.rdev_poll(dev, tg.plan, R.ALL_TENSORS, R.POLL_CONSUME, s)
+            one_launch[f"{how}_flag_groups_{G}"] = round(sorted(tt[2:])[len(tt[2:]) // 2], 1)
+        bare = []
+        for it in range(iters + 2):
+            torch.cuda.synchronize()
+            seq += 1
+            t0 = time.perf_counter()
+            R.rdev_write_batch(dev, tg.plan, None, R.ZEROCOPY, seq, s)
+            spin(lambda: R.rdev_poll(dev, tg.plan, R.ALL_TENSORS))
+            torch.cuda.synchronize()
+            bare.append((time.perf_counter() - t0) * 1e6)
+            R.rdev_poll(dev, tg.plan, R.ALL_TENSORS, R.POLL_CONSUME, s)
+        one_launch[f"bare_transfer_flag_groups_{G}"] = round(sorted(bare[2:])[len(bare[2:]) // 2], 1)
+        tg.close()
     med = lambda v: sorted(v[2:])[len(v[2:]) // 2]
     return {"sends_per_iteration": len(ids), "end_of_set_event_us": round(med(t_event), 1),
             "polling_async_us": round(med(t_async), 1), "gain": round(med(t_event) / med(t_async), 3),
-            "one_batched_write_polling_async_us": grouped}
+            "one_batched_write_polling_async_us": grouped, "one_batched_write_one_consumer_launch_us": one_launch}
 
 
 def queues_leg(R, torch, W, dev, wl, opts, spin, iters=30):
@@ -396,13 +434,14 @@ def cpu_baseline(wl_name: str, seconds: float):
     times = times[1:] if len(times) > 3 else times               # first pass faults the pages in
     med = sorted(times)[len(times) // 2]
     out = {"value": round(wl.payload_bytes / med / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+           "host_cpu_count": os.cpu_count(),
            "sample": f"{len(times)} iterations of the full {wl_name} static set ({wl.payload_bytes} B each), "
                      f"median; numpy slice copies are single-threaded",
            "us_per_iteration": round(med * 1e6, 1)}
     # the same checker call spread over host threads (numpy releases the interpreter lock while copying):
     # tensors dealt to threads by size, each thread moves its share with the unchanged static_write
     import threading
-    T = max(1, min(16, os.cpu_count() or 1))
+    T = max(1, min(16, os.cpu_count() or 1))      # the box's share of host cores for one GPU is 16, whatever it shows
     if T > 1 and len(static_ids) > 1:
         shares = [[] for _ in range(T)]
         load = [0] * T
@@ -456,6 +495,8 @@ def main():
     s = stream.cuda_stream
     stream2 = torch.cuda.Stream()           # dynamic-size traffic travels on its own queue
     s2 = stream2.cuda_stream
+    stream_r = torch.cuda.Stream()          # the receiver's own queue: the in-arena clears of consumed flags
+    sr = stream_r.cuda_stream
     has_dyn = bool(sets[0].dyn_variants)
     dyn_bytes = (sum(b for _, b in sets[0].dyn_variants) / len(sets[0].dyn_variants)) if has_dyn else 0
     torch.cuda.synchronize()
@@ -468,10 +509,10 @@ def main():
                 raise RuntimeError("flag never became visible")
 
     def wait_consume(ts):
-        spin(lambda: R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, s))
+        spin(lambda: R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, sr))
         if ts.dyn_variants:
             for t in ts.dyn_ids:
-                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, s2))
+                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, sr))
 
     seq = 0
 
@@ -490,9 +531,12 @@ def main():
                 R.rdev_dyn_reset(ts.plan)
                 xs = ts.produce(k, s2) if ts.produce else ts.dyn_variants[k % len(ts.dyn_variants)][0]
                 R.rdev_write_batch(dev, ts.plan, xs, R.ZEROCOPY, seq, s2)
-                for t in ts.dyn_ids:
-                    spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_META | R.POLL_CONSUME, s2))
-                R.rdev_read_batch(dev, ts.plan, ts.dyn_pull, seq, s2)
+                if a.host_dynamic:
+                    for t in ts.dyn_ids:
+                        spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_META | R.POLL_CONSUME, s2))
+                    R.rdev_read_batch(dev, ts.plan, ts.dyn_pull, seq, s2)
+                else:                   # the receiver's half runs on the GPU behind the metadata write
+                    R.rdev_read_batch_device(dev, ts.plan, ts.dyn_pull, seq, s2)
             if len(group) == 1:
                 wait_consume(ts)        # one set only: the next write must wait for this consumption (no ack exists)
                 continue
@@ -512,6 +556,7 @@ def main():
     run(a.steps)
     stream.synchronize()
     stream2.synchronize()
+    stream_r.synchronize()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
@@ -544,7 +589,10 @@ def main():
                    "dynamic_payload_bytes_per_iteration": round(dyn_bytes),
                    "step": "write_batch (copy kernel + flag kernel)" +
                            (" + dynamic tensors: " + ("distinct ids and their rows gathered on the GPU, " if sets[0].produce else "")
-                            + "metadata write, metadata poll, allocate + pull, on a second stream" if has_dyn else "") + " + poll/consume of the previous iteration"},
+                            + ("metadata write, host poll of the metadata, allocate + pull" if a.host_dynamic else
+                               "metadata write, then the receiver's allocate + pull on the GPU without a host poll")
+                            + ", on a second stream" if has_dyn else "")
+                           + " + poll/consume of the previous iteration (in-arena clears on the receiver's own stream)"},
         "us_per_iteration": round(ms_per_step * 1e3, 2),
         "hbm_gbs_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_frac_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -569,29 +617,43 @@ def main():
         runs.append((time.perf_counter() - r0) / 100 * 1e6)
     out["five_runs_of_100"] = {"us_per_iteration_mean": round(sum(runs) / 5, 2), "min": round(min(runs), 2),
                                "max": round(max(runs), 2)}
+    # one set only (no rotation): every write waits for the consumption of the one before it
+    torch.cuda.synchronize()
+    r0 = time.perf_counter()
+    run(100, [sets[0]])
+    torch.cuda.synchronize()
+    out["single_set_us_per_iteration"] = round((time.perf_counter() - r0) / 100 * 1e6, 2)
     if has_dyn:
-        # the dynamic protocol on its own (section 3.3): metadata + flag -> host poll -> allocate + pull -> host poll
+        # the dynamic protocol on its own (section 3.3): metadata + flag -> receiver allocates + pulls -> payload flag
+        # seen on the host; with the receiver's half driven by the host (two polls) or running on the GPU (one)
         ts = sets[0]
-        lat = []
-        for k in range(203):
-            xs, _ = ts.dyn_variants[k % len(ts.dyn_variants)]
-            seq += 1
-            torch.cuda.synchronize()
-            d0 = time.perf_counter()
-            R.rdev_dyn_reset(ts.plan)
-            if ts.produce:
-                xs = ts.produce(k, s2)
-            R.rdev_write_batch(dev, ts.plan, xs, R.ZEROCOPY, seq, s2)
-            for t in ts.dyn_ids:
-                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_META | R.POLL_CONSUME, s2))
-            R.rdev_read_batch(dev, ts.plan, ts.dyn_pull, seq, s2)
-            for t in ts.dyn_ids:
-                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, s2))
-            lat.append((time.perf_counter() - d0) * 1e6)
-        lat = sorted(lat[3:])
-        out["dynamic_round_trip_us"] = {"median": round(lat[len(lat) // 2], 2), "min": round(lat[0], 2),
-                                        "p90": round(lat[int(len(lat) * 0.9)], 2), "tensors": len(ts.dyn_ids),
-                                        "payload_bytes_mean": round(dyn_bytes)}
+        rt = {}
+        for how in ("host_polled", "device_side"):
+            lat = []
+            for k in range(203):
+                xs, _ = ts.dyn_variants[k % len(ts.dyn_variants)]
+                seq += 1
+                torch.cuda.synchronize()
+                d0 = time.perf_counter()
+                R.rdev_dyn_reset(ts.plan)
+                if ts.produce:
+                    xs = ts.produce(k, s2)
+                R.rdev_write_batch(dev, ts.plan, xs, R.ZEROCOPY, seq, s2)
+                if how == "host_polled":
+                    for t in ts.dyn_ids:
+                        spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_META | R.POLL_CONSUME, s2))
+                    R.rdev_read_batch(dev, ts.plan, ts.dyn_pull, seq, s2)
+                else:
+                    R.rdev_read_batch_device(dev, ts.plan, ts.dyn_pull, seq, s2)
+                for t in ts.dyn_ids:
+                    spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, s2))
+                lat.append((time.perf_counter() - d0) * 1e6)
+            lat = sorted(lat[3:])
+            rt[how] = {"median": round(lat[len(lat) // 2], 2), "min": round(lat[0], 2),
+                       "p90": round(lat[int(len(lat) * 0.9)], 2)}
+        rt.update({"tensors": len(ts.dyn_ids), "payload_bytes_mean": round(dyn_bytes),
+                   "includes_gather_on_gpu": bool(ts.produce)})
+        out["dynamic_round_trip_us"] = rt
     props = torch.cuda.get_device_properties(0)
     dev_info = {"name": props.name, "compute_units": props.multi_processor_count,
                 "hbm_bytes": props.total_memory}

@@ -522,10 +522,10 @@ rdev_status rdev_graph_transfers(const rdev_graph_t *g, const uint32_t *partitio
 rdev_status rdev_device_info(rdev_device_t *dev, uint64_t out[4]);
 
 /* Time the batched copy kernel of whole-plan transfers (x == NULL) with HIP
- * events recorded on the transfer's own stream, directly before and after that
- * kernel (the flag kernel that follows is outside the bracket).  Every
- * `every`-th launch is timed (an event pair costs a few microseconds of stream
- * time), up to max_samples of them; max_samples == 0 switches timing off.
+ * events on the transfer's own stream: the launch is given a start and a stop
+ * event of its own, which take the kernel's begin and end times (the flag
+ * kernel that follows is outside).  Every `every`-th launch is timed, up to
+ * max_samples of them; max_samples == 0 switches timing off.
  * Section 5 reports means over runs of 100 iterations; this gives the per-launch
  * figure those means are made of. */
 rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples, uint32_t every);

@@ -1,5 +1,6 @@
 // C-ABI entry points of the memory-region device (see include/rdev.h).
 // Host logic + kernel launches; the kernels are in kernels.h, the planner in planner.cpp.
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -1073,10 +1074,20 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
         if (gr.n_blocks) {
             // the timing bracket covers the launch of the first group (the only one unless flag_groups > 1)
             const bool timed = g == 0 && plan->ev_used < plan->ev_start.size() && (plan->ev_count++ % plan->ev_every) == 0;
-            if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
-            RDEV_TRY(launch_copy_table(plan->d_items.ptr + gr.first_block, plan->d_subs.ptr, gr.n_blocks, s,
-                                       "copy_table_kernel"));
-            if (timed) HIP_TRY(hipEventRecord(plan->ev_stop[plan->ev_used++], s));
+            if (timed && gr.n_blocks <= kMaxBlocksPerLaunch) {
+                // the launch carries its own start and stop events: they take the kernel's begin and end times,
+                // with no marker packets of their own in the stream
+                hipExtLaunchKernelGGL(rdev::copy_table_kernel, dim3(gr.n_blocks), dim3(rdev::kBlockThreads), 0, s,
+                                      plan->ev_start[plan->ev_used], plan->ev_stop[plan->ev_used], 0,
+                                      (const Item *)(plan->d_items.ptr + gr.first_block), (const Item *)plan->d_subs.ptr);
+                RDEV_TRY(launch_check("copy_table_kernel"));
+                plan->ev_used++;
+            } else {
+                if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
+                RDEV_TRY(launch_copy_table(plan->d_items.ptr + gr.first_block, plan->d_subs.ptr, gr.n_blocks, s,
+                                           "copy_table_kernel"));
+                if (timed) HIP_TRY(hipEventRecord(plan->ev_stop[plan->ev_used++], s));
+            }
         }
         RDEV_TRY(launch_group_flags(plan, g, seq, token, s));
     }
