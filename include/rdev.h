@@ -392,7 +392,7 @@ rdev_status rdev_consume_reduce_max(rdev_device_t *dev, rdev_plan_t *plan, uint3
                                     rdev_consume_result *out, void *stream);
 
 /* The same consumer for a list of static tensors in one launch per 32 tensors:
- * out[i] belongs to tensor_ids[i].  Tensors are cut into 256 KiB units that the
+ * out[i] belongs to tensor_ids[i].  Tensors are cut into 64 KiB units that the
  * workgroups take in list order, so tensors early in the list are reduced first.
  * With max_spins > 0 every unit first waits (at most max_spins acquire loads) for
  * its tensor's in-arena flag; enqueued on a second stream behind a delivery that

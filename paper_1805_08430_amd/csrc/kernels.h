@@ -154,12 +154,21 @@ __global__ __launch_bounds__(kBlockThreads) void copy_inline_kernel(InlineBatch 
 
 // flag <- value for a table of tensors (in-arena words), then ONE host-visible word for the whole table.
 // The payload these flags announce was written by the kernel enqueued before this
-// one on the same stream, so it is already visible when this kernel starts.
+// one on the same stream, so it is already visible when this kernel starts: the
+// stores here need the right scope but no cache write-back of their own.
 // The host is told with one word for the whole table (a delivery token):
 // per-tensor host words would be thousands of separate writes across the host
-// link for the many-small-tensor sets.  One workgroup walks the table, so the
-// token can be stored after every in-arena word: a receiver that has seen the
-// token may clear those words from any other stream without meeting a late store.
+// link for the many-small-tensor sets.  One workgroup walks the table, and the
+// token is stored only after every in-arena word has been acknowledged: the
+// agent-scope stores write through, each wave waits until its own outstanding
+// stores have been acknowledged (wait_stores_acked: the wait alone, without the
+// L2 write-back a release fence of agent or system scope would add), then the
+// barrier, and one lane stores the token behind it.  A receiver that has seen the token may therefore clear
+// the in-arena words from any other stream without meeting a late store.
+// s_waitcnt vmcnt(0): this wave's vector-memory stores (and loads) issued so far have completed.  The operand is the
+// gfx9 encoding with the export and LDS/scalar counters left at "do not wait".
+__device__ __forceinline__ void wait_stores_acked() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 constexpr uint32_t kFlagTableThreads = 1024;
 __global__ __launch_bounds__(kFlagTableThreads) void flag_table_kernel(const FlagEnt *__restrict__ ents, uint32_t n,
                                                                         uint32_t value, uint32_t *batch_word,
@@ -167,8 +176,9 @@ __global__ __launch_bounds__(kFlagTableThreads) void flag_table_kernel(const Fla
     for (uint32_t i = threadIdx.x; i < n; i += kFlagTableThreads)
         __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (!batch_word) return;
+    wait_stores_acked();
     __syncthreads();
-    if (threadIdx.x == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (threadIdx.x == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 constexpr uint32_t kFlagInlineMax = 32;
@@ -179,13 +189,16 @@ struct InlineFlags {
     uint32_t value;
 };
 
-// the same for a few tensors named in the kernel arguments, one host-visible word each (stored after the in-arena word)
+// the same for a few tensors named in the kernel arguments, one host-visible word each, stored once the lane's
+// in-arena store has been acknowledged
 __global__ void flag_inline_kernel(InlineFlags f, uint32_t *mirror) {
     const uint32_t i = threadIdx.x;
     if (i >= f.n) return;
     __hip_atomic_store(f.arena_flag[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (mirror)
-        __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (mirror) {
+        wait_stores_acked();
+        __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
 }
 
 // Dynamic path, sender side: 120 bytes of metadata into the receiver's slot
@@ -452,8 +465,9 @@ __global__ __launch_bounds__(kFlagTableThreads) void rpc_flag_kernel(const FlagE
         const uint32_t seq = ((const rdev_meta *)hdr_ptrs[i])->seq;
         __hip_atomic_store(ents[i].arena_flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    wait_stores_acked();
     __syncthreads();
-    if (threadIdx.x == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (threadIdx.x == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // ---- producer of the sparse case: distinct ids (ascending) and their rows ----
@@ -576,7 +590,15 @@ __device__ __forceinline__ void consume_slice(const uint8_t *payload, uint64_t b
             m = o > m ? o : m;
         }
     };
-    for (uint64_t i = v0 + first; i < v1; i += stride) {
+    uint64_t i = v0 + first;
+    for (; i + 7 * stride < v1; i += 8 * stride) {      // eight loads in flight per lane: the loop is latency-bound otherwise
+        v4u v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load(p + i + k * stride);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { take(v[k].x); take(v[k].y); take(v[k].z); take(v[k].w); }
+    }
+    for (; i < v1; i += stride) {
         const v4u v = __builtin_nontemporal_load(p + i);
         take(v.x); take(v.y); take(v.z); take(v.w);
     }
@@ -629,7 +651,7 @@ __global__ __launch_bounds__(kConsumeThreads) void consume_reduce_max_kernel(con
 // delivery that is still in flight: tensors whose flag is up are reduced while later ones are still moving.
 // A unit whose wait runs out is skipped; its tensor's result keeps status 1.  Every workgroup ends.
 constexpr uint32_t kConsumeBatchMax = 32;
-constexpr uint32_t kConsumeUnitBytes = 256 * 1024;
+constexpr uint32_t kConsumeUnitBytes = 64 * 1024;
 constexpr uint32_t kConsumeTableMaxBlocks = 256;     // when the kernel may have to wait (waiting workgroups hold wave slots)
 
 struct ConsumeEnt {

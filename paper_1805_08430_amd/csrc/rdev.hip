@@ -276,13 +276,18 @@ rdev_status launch_check(const char *what) {
 // another stream and may still be pending, s waits for it: a late clear must not wipe the flags of this delivery.
 rdev_status before_delivery(rdev_plan_t *plan, hipStream_t s) {
     if (plan->clear_pending && plan->clear_stream != s) {
-        const hipError_t q = hipEventQuery(plan->ev_clear);
+        // The clear is one tiny kernel that was enqueued on an otherwise idle stream: it is normally done by now, or
+        // within microseconds.  Ask on the host for a short while first; a wait inside stream s is the fallback, as
+        // a cross-stream dependency costs the delivery more than the clear itself takes.
+        hipError_t q = hipErrorNotReady;
+        for (int spin = 0; spin < 100 && q == hipErrorNotReady; ++spin) q = hipEventQuery(plan->ev_clear);
         if (q == hipErrorNotReady) {
             (void)hipGetLastError();
             HIP_TRY(hipStreamWaitEvent(s, plan->ev_clear, 0));
         } else if (q != hipSuccess) {
             return fail(RDEV_E_HIP, std::string("hipEventQuery: ") + hipGetErrorString(q));
         }
+        (void)hipGetLastError();
     }
     plan->clear_pending = false;
     plan->delivery_stream = s;
@@ -1536,7 +1541,7 @@ static rdev_status consume_checked(rdev_plan_t *plan, uint32_t idx, uint32_t max
     const rdev_placement &p = plan->pl[idx];
     hipLaunchKernelGGL(rdev::consume_init_kernel, dim3(1), dim3(64), 0, s, out, 1u);
     RDEV_TRY(launch_check("consume_init_kernel"));
-    const uint64_t per_block = (uint64_t)rdev::kConsumeThreads * 16 * 16;        // 64 KiB of payload per workgroup pass
+    const uint64_t per_block = (uint64_t)rdev::kConsumeThreads * 16 * 16;        // 64 KiB of payload per workgroup
     const uint32_t cap = max_spins ? rdev::kConsumeMaxBlocks : rdev::kConsumeMaxBlocksNoWait;
     uint32_t grid = (uint32_t)std::min<uint64_t>(cap, (p.bytes + per_block - 1) / per_block);
     if (!grid) grid = 1;
