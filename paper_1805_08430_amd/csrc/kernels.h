@@ -556,21 +556,25 @@ __global__ void consume_init_kernel(rdev_consume_result *out, uint32_t n) {
     if (i < n) consume_init_one(out + i);
 }
 
-// One workgroup's wait for a tensor's in-arena flag: at most max_spins acquire loads by one lane, the answer
-// shared with the others.  Returns the flag value seen, 0 = gave up.
+// One workgroup's wait for a tensor's in-arena flag: at most max_spins loads by one lane (agent scope, relaxed: they
+// go past the caches and cost no invalidation each), the answer shared with the others; once the flag is up every
+// wave makes ONE acquire, so that none of the payload is served from lines an earlier iteration left in the caches.
+// Returns the flag value seen, 0 = gave up.
 __device__ __forceinline__ uint32_t consume_wait(const uint32_t *flag, uint32_t max_spins, uint32_t *s_seen) {
     __syncthreads();                                    // s_seen may still be read from an earlier wait
     if (threadIdx.x == 0) {
         uint32_t v = 0;
         for (uint32_t k = 0; k < max_spins; ++k) {
-            v = __hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+            v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (v) break;
             __builtin_amdgcn_s_sleep(8);
         }
         *s_seen = v;
     }
     __syncthreads();
-    return *s_seen;
+    const uint32_t seen = *s_seen;
+    if (seen) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return seen;
 }
 
 // Reduce 16-byte vectors [v0, v1) of payload (lane i takes v0 + i, v0 + i + stride, ...), plus the up to three
@@ -617,10 +621,16 @@ __device__ __forceinline__ void consume_slice(const uint8_t *payload, uint64_t b
     __syncthreads();
     if (threadIdx.x == 0) {
         for (uint32_t w = 1; w < kConsumeThreads / 64; ++w) { m = s_max[w] > m ? s_max[w] : m; sum += s_sum[w]; }
+        // Everything the workgroups exchange goes through agent-scope atomics, which are performed at the point all
+        // compute dies share; so no cache write-back or invalidation is needed around the arrival count, only that
+        // this lane's two contributions have been performed before it counts itself in.
         __hip_atomic_fetch_max((uint32_t *)&out->max, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_fetch_add((unsigned long long *)&out->word_sum, (unsigned long long)sum, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        wait_stores_acked();
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (prev + 1 == arrivals_needed) {               // last one: publish
             const uint32_t key = __hip_atomic_load((uint32_t *)&out->max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ((uint32_t *)&out->max)[0] = ord2f(key);
@@ -670,13 +680,15 @@ __global__ __launch_bounds__(kConsumeThreads) void consume_table_kernel(ConsumeB
     __shared__ uint32_t s_seen;
     __shared__ uint32_t s_max[kConsumeThreads / 64];
     __shared__ uint64_t s_sum[kConsumeThreads / 64];
-    uint32_t k = 0;
+    uint32_t k = 0, waited_k = 0xFFFFFFFFu, seen = 0;
     for (uint32_t u = blockIdx.x; u < b.n_units; u += gridDim.x) {
         while (u >= b.e[k].first_unit + b.e[k].n_units) ++k;          // units ascend, so does the tensor
         const ConsumeEnt &e = b.e[k];
-        uint32_t seen = 0;
         if (b.max_spins) {
-            seen = consume_wait(e.flag, b.max_spins, &s_seen);
+            if (k != waited_k) {                                      // one wait per tensor and workgroup
+                seen = consume_wait(e.flag, b.max_spins, &s_seen);
+                waited_k = k;
+            }
             if (!seen) continue;
         }
         const uint32_t j = u - e.first_unit;

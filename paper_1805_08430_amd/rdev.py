@@ -259,9 +259,19 @@ def make_xfer(tensor_id: int, src: Optional[int] = None, dtype: int = 0, dims: S
     return x
 
 
-def _xfers(x: Optional[Sequence[Xfer]]):
+class XferArray:
+    """A batch marshalled once (a C array of rdev_xfer) for callers that send the same batch every iteration."""
+    __slots__ = ("arr", "n")
+
+    def __init__(self, xs: Sequence[Xfer]):
+        self.arr, self.n = (Xfer * len(xs))(*xs), len(xs)
+
+
+def _xfers(x):
     if not x:
         return None, 0
+    if isinstance(x, XferArray):
+        return x.arr, x.n
     return (Xfer * len(x))(*x), len(x)
 
 
