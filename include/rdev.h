@@ -525,7 +525,10 @@ rdev_status rdev_device_info(rdev_device_t *dev, uint64_t out[4]);
  * events on the transfer's own stream: the launch is given a start and a stop
  * event of its own, which take the kernel's begin and end times (the flag
  * kernel that follows is outside).  Every `every`-th launch is timed, up to
- * max_samples of them; max_samples == 0 switches timing off.
+ * max_samples of them; max_samples == 0 switches timing off.  Changing
+ * max_samples waits for the device and re-creates the events; calling again
+ * with the same max_samples only re-arms: no wait, samples not read yet are
+ * dropped, and the caller must have waited for launches that were being timed.
  * Section 5 reports means over runs of 100 iterations; this gives the per-launch
  * figure those means are made of. */
 rdev_status rdev_plan_profile(rdev_plan_t *plan, uint32_t max_samples, uint32_t every);

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librdev.so")
 SOURCES = ["rdev.hip", "planner.cpp", "graph.cpp"]
-HEADERS = ["kernels.h", "planner.h"]
+HEADERS = ["kernels.h", "copy_kernel.h", "copy_table.h", "planner.h"]
 
 
 def lib_path() -> str:
