@@ -65,6 +65,8 @@ def parse():
     ap.add_argument("--small-bytes", type=int, default=0)
     ap.add_argument("--flag-groups", type=int, default=0,
                     help="launches per whole-plan transfer, each followed by its tensors' flags (default one)")
+    ap.add_argument("--misalign", action="store_true",
+                    help="vgg16 only: source k starts k mod 16 bytes off a 16-byte boundary (all alignment classes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-modes", action="store_true", help="skip the untimed comparison with the copying modes")
     ap.add_argument("--mode-steps", type=int, default=60)
@@ -484,7 +486,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     R.lib()
-    wl = {**W.CONFIGS, **W.EXTRA_CONFIGS}[a.workload]()
+    wl = W.vgg16(misalign=True) if (a.misalign and a.workload == "vgg16") else {**W.CONFIGS, **W.EXTRA_CONFIGS}[a.workload]()
     payload = wl.payload_bytes
     rotate = a.rotate or max(2, -(-(1 << 30) // max(2 * payload, 1)))
     rotate = min(rotate, 64)
@@ -510,11 +512,13 @@ def main():
             if spins > 50_000_000:
                 raise RuntimeError("flag never became visible")
 
-    def wait_consume(ts):
-        spin(lambda: R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, sr))
+    def wait_consume(ts, alone=False):
+        # rotating sets: the clears travel on the receiver's own stream, off the next delivery's path; one set alone:
+        # the next delivery has to wait for the clear anyway, and the delivery's own stream is the cheapest order
+        spin(lambda: R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, s if alone else sr))
         if ts.dyn_variants:
             for t in ts.dyn_ids:
-                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, sr))
+                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, s2 if alone else sr))
 
     seq = 0
 
@@ -540,7 +544,7 @@ def main():
                 else:                   # the receiver's half runs on the GPU behind the metadata write
                     R.rdev_read_batch_device(dev, ts.plan, ts.dyn_pull, seq, s2)
             if len(group) == 1:
-                wait_consume(ts)        # one set only: the next write must wait for this consumption (no ack exists)
+                wait_consume(ts, True)  # one set only: the next write must wait for this consumption (no ack exists)
                 continue
             if prev is not None:
                 wait_consume(prev)

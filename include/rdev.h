@@ -310,7 +310,8 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
  * seq.  The arena ends up byte for byte as after rdev_poll(RDEV_POLL_META |
  * RDEV_POLL_CONSUME) + rdev_read_batch; no host poll of the metadata is needed,
  * and rdev_poll(tensor) later reports the payload as usual.
- *   x, n : 1..8 dynamic tensors (only tensor_id is read).
+ *   x, n : 1..8 dynamic tensors.  Only tensor_id matters; ndims/dtype/dims, when given, are a size hint (an
+ *          upper bound is fine) that shapes the launch and nothing else.
  * The checks the host path makes are made on the device: metadata flag set,
  * sender range inside a registered arena, heap space, no overlap.  If any entry
  * fails, nothing of the batch moves and no flag changes; rdev_recv_status tells.

@@ -46,6 +46,15 @@ struct PostBatch {                           // after a pull: record the offset,
 // gfx9 encoding with the export and LDS/scalar counters left at "do not wait".
 __device__ __forceinline__ void wait_stores_acked() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// Stores that every compute die (and a later kernel on any of them) must see without a cache write-back: agent-scope
+// relaxed atomic stores write through.  Used for the few words of records and flags; payloads go through copy_span.
+__device__ __forceinline__ void store_through(uint32_t *p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_through(uint64_t *p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // flag <- value for a table of tensors (in-arena words), then ONE host-visible word for the whole table.
 // The payload these flags announce was written by the kernel enqueued before this
 // one on the same stream, so it is already visible when this kernel starts: the
@@ -108,13 +117,14 @@ __global__ __launch_bounds__(64) void meta_write_kernel(MetaBatch b, uint32_t *m
             const uint64_t v = (t < 4) ? d0 * b.row_bytes[k] : d0;
             w = (t & 1) ? (uint32_t)(v >> 32) : (uint32_t)v;
         }
-        slot[t] = w;
-        host[t] = w;
+        store_through(slot + t, w);
+        host[t] = w;                    // host-coherent memory: not cached on the device
     }
-    __syncthreads();
+    // the flag goes out once every word of the record has been acknowledged (one wave: its own wait is enough)
+    wait_stores_acked();
     if (t == 0) {
-        __hip_atomic_store(slot + 31, b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(mirror_flags + b.flag_idx[k], b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        store_through(slot + 31, b.seq);
+        __hip_atomic_store(mirror_flags + b.flag_idx[k], b.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -122,10 +132,12 @@ __global__ __launch_bounds__(64) void meta_write_kernel(MetaBatch b, uint32_t *m
 __global__ void post_pull_kernel(PostBatch b, uint32_t *mirror_flags, rdev_meta *mirror_meta) {
     const uint32_t i = threadIdx.x;
     if (i >= b.n) return;
-    *(uint64_t *)(b.slot[i] + 88) = b.dst_offset[i];
+    // the payload was written by the kernel before this one; within this kernel the offset must be out before the flag
+    store_through((uint64_t *)(b.slot[i] + 88), b.dst_offset[i]);
     mirror_meta[b.meta_idx[i]].dst_offset = b.dst_offset[i];
-    __hip_atomic_store((uint32_t *)(b.slot[i] + 120), b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(mirror_flags + b.flag_idx[i], b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    wait_stores_acked();
+    store_through((uint32_t *)(b.slot[i] + 120), b.seq);
+    __hip_atomic_store(mirror_flags + b.flag_idx[i], b.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // ---- dynamic path, receiver side, with the sizes taken on the device (section 3.3) ----
@@ -139,7 +151,8 @@ __global__ void post_pull_kernel(PostBatch b, uint32_t *mirror_flags, rdev_meta 
 // with the same code; a batch that fails any check moves nothing.
 
 constexpr uint32_t kRecvMax = 8;                 // tensors per launch
-constexpr uint32_t kRecvMaxBlocks = 2048;
+constexpr uint32_t kRecvMaxBlocks = 2048;           // with a size hint from the caller
+constexpr uint32_t kRecvBlocksNoHint = 256;       // without: the workgroups stride over whatever the records say
 
 struct ArenaEnt {                                // device table of the registered arenas
     uint8_t *base;
@@ -160,8 +173,10 @@ struct RecvEnt {
     uint32_t dst_arena;
     uint32_t meta_idx, flag_idx;                 // host-visible copies: record, flag pair (2*index)
 };
+constexpr uint32_t kArenaArgs = 16;              // arenas 0..15 travel in the kernel arguments (no dependent table load)
 struct RecvBatch {
     RecvEnt e[kRecvMax];
+    ArenaEnt arena[kArenaArgs];
     uint64_t align;
     uint32_t n, seq, epoch, chunk, n_arenas, call_id;
 };
@@ -203,8 +218,9 @@ __device__ __forceinline__ void recv_layout(const RecvBatch &b, const ArenaEnt *
                 if (b.e[j].heap_word == b.e[k].heap_word) ptr = L.new_ptr[j];      // same arena earlier in the batch
             const uint64_t nb = s_bytes[k], need = (nb + b.align - 1) & ~(b.align - 1);
             if (!s_flag[k]) { st = RDEV_NOT_READY; break; }
-            if (s_src_arena[k] >= b.n_arenas || !arenas[s_src_arena[k]].bytes) { st = RDEV_E_RANGE; break; }
-            const ArenaEnt sa = arenas[s_src_arena[k]];
+            if (s_src_arena[k] >= b.n_arenas) { st = RDEV_E_RANGE; break; }
+            const ArenaEnt sa = s_src_arena[k] < kArenaArgs ? b.arena[s_src_arena[k]] : arenas[s_src_arena[k]];
+            if (!sa.bytes) { st = RDEV_E_RANGE; break; }
             if (s_src_off[k] > sa.bytes || nb > sa.bytes - s_src_off[k]) { st = RDEV_E_RANGE; break; }
             if (need < nb || ptr > b.e[k].heap_bytes || need > b.e[k].heap_bytes - ptr) { st = RDEV_E_NOMEM; break; }
             const uint64_t dst_off = b.e[k].heap_offset + ptr;
@@ -253,22 +269,26 @@ __global__ __launch_bounds__(64) void recv_post_kernel(RecvBatch b, const ArenaE
     const uint32_t t = threadIdx.x;
     if (L.status == RDEV_OK && t < b.n) {
         uint8_t *slot = b.e[t].slot;
-        *(uint64_t *)(slot + 88) = L.dst_offset[t];
+        store_through((uint64_t *)(slot + 88), L.dst_offset[t]);
         mirror_meta[b.e[t].meta_idx].dst_offset = L.dst_offset[t];
-        __hip_atomic_store((uint32_t *)(slot + 124), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // metadata consumed
+        store_through((uint32_t *)(slot + 124), 0u);                     // metadata consumed
         __hip_atomic_store(mirror_flags + b.e[t].flag_idx + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         bool last = true;                                                // last entry of its arena stores the heap pointer
         for (uint32_t j = t + 1; j < b.n; ++j)
             if (b.e[j].heap_word == b.e[t].heap_word) last = false;
-        if (last) heap[b.e[t].heap_word] = HeapWord{L.new_ptr[t], b.epoch, 0};
-        __hip_atomic_store((uint32_t *)(slot + 120), b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(mirror_flags + b.e[t].flag_idx, b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (last) {
+            store_through(&heap[b.e[t].heap_word].ptr, L.new_ptr[t]);
+            store_through(&heap[b.e[t].heap_word].epoch, b.epoch);
+        }
+        wait_stores_acked();                                             // offset and cleared flag first, then payload-complete
+        store_through((uint32_t *)(slot + 120), b.seq);
+        __hip_atomic_store(mirror_flags + b.e[t].flag_idx, b.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
-    __syncthreads();
     if (t == 0) {
         status[0] = (uint32_t)L.status;
         status[1] = L.bad;
-        __hip_atomic_store(status + 2, b.call_id, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        wait_stores_acked();
+        __hip_atomic_store(status + 2, b.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 

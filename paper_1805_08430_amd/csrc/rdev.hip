@@ -1349,7 +1349,10 @@ rdev_status rdev_read_batch_device(rdev_device_t *dev, rdev_plan_t *plan, const 
         b.align = plan->opts.align;
         b.n_arenas = (uint32_t)dev->arenas.size();
         b.call_id = ++plan->recv_calls;
-        uint64_t room = 0;
+        for (uint32_t a = 0; a < rdev::kArenaArgs && a < dev->arenas.size(); ++a)
+            b.arena[a] = rdev::ArenaEnt{dev->arenas[a].base, dev->arenas[a].bytes};
+        uint64_t room = 0, hint = 0;
+        bool hinted = true;
         for (uint32_t k = 0; k < b.n; ++k) {
             const uint32_t i = idx[first + k];
             const rdev_placement &p = plan->pl[i];
@@ -1366,10 +1369,18 @@ rdev_status rdev_read_batch_device(rdev_device_t *dev, rdev_plan_t *plan, const 
             e.flag_idx = 2 * i;
             room += al.heap_bytes;
             plan->polled_valid[plan->dyn_index[i]] = 0;
+            // optional size hint: dims given with the entry (an upper bound is fine) shape the launch, nothing else
+            uint64_t hb = 0;
+            std::string ignore;
+            const rdev_xfer &xe = x[first + k];
+            if (xe.ndims && rdev::tensor_bytes(xe.dtype, xe.ndims, xe.dims, &hb, ignore) == RDEV_OK) hint += hb;
+            else hinted = false;
         }
-        // the payload sizes are not known here: enough workgroups for what the heaps could take, within a bound
-        const uint64_t want = room / plan->opts.chunk_bytes + 1;
-        const uint32_t grid = (uint32_t)std::min<uint64_t>(want, rdev::kRecvMaxBlocks);
+        // The payload sizes are not known on the host.  The workgroups stride over the chunks the records call for, so
+        // any grid is correct; a hinted batch gets one workgroup per chunk, an unhinted one a modest fixed number
+        // (idle workgroups still cost a layout pass each and take wave slots from whatever else is running).
+        const uint64_t want = (hinted ? hint : room) / plan->opts.chunk_bytes + b.n;
+        const uint32_t grid = (uint32_t)std::min<uint64_t>(want, hinted ? rdev::kRecvMaxBlocks : rdev::kRecvBlocksNoHint);
         hipLaunchKernelGGL(rdev::recv_pull_kernel, dim3(grid), dim3(rdev::kBlockThreads), 0, s, b, dev->d_arenas, plan->d_heap.ptr);
         RDEV_TRY(launch_check("recv_pull_kernel"));
         hipLaunchKernelGGL(rdev::recv_post_kernel, dim3(1), dim3(64), 0, s, b, dev->d_arenas, plan->d_heap.ptr,

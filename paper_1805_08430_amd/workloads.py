@@ -188,7 +188,9 @@ def alexnet() -> Workload:
                     "8 weight + 8 bias tensors, ungrouped shapes as listed")
 
 
-def vgg16() -> Workload:
+def vgg16(misalign: bool = False) -> Workload:
+    """misalign=True: the same tensors, but source k starts k mod 16 bytes off a 16-byte boundary, so that every
+    alignment class of the copy routine (16-byte, 4-byte, byte) is exercised on full-size tensors."""
     seed = SEED_BASE + 2
     chans = [(3, 64), (64, 64), (64, 128), (128, 128), (128, 256), (256, 256), (256, 256),
              (256, 512), (512, 512), (512, 512), (512, 512), (512, 512), (512, 512)]
@@ -196,6 +198,12 @@ def vgg16() -> Workload:
     layers += [("fc14", (4096, 25088)), ("fc15", (4096, 4096)), ("fc16", (1000, 4096))]
     tensors = _wb_list(layers, 8)
     sb = _pack_sources(tensors, 1, 256)
+    if misalign:
+        shift = 0
+        for k, t in enumerate(tensors):
+            shift += 16
+            t.src_offset += shift + (k % 16)          # keeps the sources apart and walks through all 16 offsets
+        sb = [sb[0] + shift + 64]
     return Workload("vgg16", seed, tensors, 1, 8, sb, "normal",
                     "16 weight + 16 bias tensors, tensor i -> receiver arena i mod 8")
 

@@ -90,6 +90,14 @@ def test_full_size_configs(name):
     _run_static(wl, iters=1, heap=1 << 20)
 
 
+def test_vgg16_with_every_source_misalignment():
+    """Full-size tensors through the 4-byte-aligned and the byte-misaligned copy paths (the listed configs pack their
+    sources at 256 bytes, which only exercises the 16-byte path)."""
+    wl = W.vgg16(misalign=True)
+    assert sorted({t.src_offset % 16 for t in wl.tensors}) == list(range(16))
+    _run_static(wl, iters=1)
+
+
 def test_exhaustive_small_sizes_and_misalignments():
     """sizes 0..67 x source misalignment 0..15, one plan per misalignment."""
     from gpu_harness import GpuRun
