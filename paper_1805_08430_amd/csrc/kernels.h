@@ -54,6 +54,14 @@ __device__ __forceinline__ void store_through(uint32_t *p, uint32_t v) {
 __device__ __forceinline__ void store_through(uint64_t *p, uint64_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// The same towards pinned host memory.  A plain store there may sit in a device cache until the kernel ends and be
+// overtaken by a flag stored with system scope; these leave the device in program order.
+__device__ __forceinline__ void store_host(uint32_t *p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ void store_host(uint64_t *p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 
 // flag <- value for a table of tensors (in-arena words), then ONE host-visible word for the whole table.
 // The payload these flags announce was written by the kernel enqueued before this
@@ -118,13 +126,13 @@ __global__ __launch_bounds__(64) void meta_write_kernel(MetaBatch b, uint32_t *m
             w = (t & 1) ? (uint32_t)(v >> 32) : (uint32_t)v;
         }
         store_through(slot + t, w);
-        host[t] = w;                    // host-coherent memory: not cached on the device
+        store_host(host + t, w);
     }
     // the flag goes out once every word of the record has been acknowledged (one wave: its own wait is enough)
     wait_stores_acked();
     if (t == 0) {
         store_through(slot + 31, b.seq);
-        __hip_atomic_store(mirror_flags + b.flag_idx[k], b.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        store_host(mirror_flags + b.flag_idx[k], b.seq);
     }
 }
 
@@ -134,10 +142,10 @@ __global__ void post_pull_kernel(PostBatch b, uint32_t *mirror_flags, rdev_meta 
     if (i >= b.n) return;
     // the payload was written by the kernel before this one; within this kernel the offset must be out before the flag
     store_through((uint64_t *)(b.slot[i] + 88), b.dst_offset[i]);
-    mirror_meta[b.meta_idx[i]].dst_offset = b.dst_offset[i];
+    store_host((uint64_t *)&mirror_meta[b.meta_idx[i]].dst_offset, b.dst_offset[i]);
     wait_stores_acked();
     store_through((uint32_t *)(b.slot[i] + 120), b.seq);
-    __hip_atomic_store(mirror_flags + b.flag_idx[i], b.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    store_host(mirror_flags + b.flag_idx[i], b.seq);
 }
 
 // ---- dynamic path, receiver side, with the sizes taken on the device (section 3.3) ----
@@ -270,9 +278,9 @@ __global__ __launch_bounds__(64) void recv_post_kernel(RecvBatch b, const ArenaE
     if (L.status == RDEV_OK && t < b.n) {
         uint8_t *slot = b.e[t].slot;
         store_through((uint64_t *)(slot + 88), L.dst_offset[t]);
-        mirror_meta[b.e[t].meta_idx].dst_offset = L.dst_offset[t];
+        store_host((uint64_t *)&mirror_meta[b.e[t].meta_idx].dst_offset, L.dst_offset[t]);
         store_through((uint32_t *)(slot + 124), 0u);                     // metadata consumed
-        __hip_atomic_store(mirror_flags + b.e[t].flag_idx + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        store_host(mirror_flags + b.e[t].flag_idx + 1, 0u);
         bool last = true;                                                // last entry of its arena stores the heap pointer
         for (uint32_t j = t + 1; j < b.n; ++j)
             if (b.e[j].heap_word == b.e[t].heap_word) last = false;
@@ -282,13 +290,13 @@ __global__ __launch_bounds__(64) void recv_post_kernel(RecvBatch b, const ArenaE
         }
         wait_stores_acked();                                             // offset and cleared flag first, then payload-complete
         store_through((uint32_t *)(slot + 120), b.seq);
-        __hip_atomic_store(mirror_flags + b.e[t].flag_idx, b.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        store_host(mirror_flags + b.e[t].flag_idx, b.seq);
     }
     if (t == 0) {
-        status[0] = (uint32_t)L.status;
-        status[1] = L.bad;
+        store_host(status, (uint32_t)L.status);
+        store_host(status + 1, L.bad);
         wait_stores_acked();
-        __hip_atomic_store(status + 2, b.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        store_host(status + 2, b.call_id);
     }
 }
 

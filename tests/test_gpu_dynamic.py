@@ -212,6 +212,39 @@ def test_device_side_receive_tiny_and_lstm():
     g.close()
 
 
+def test_host_visible_record_is_never_older_than_its_flag():
+    """Many back-to-back rounds with a different size every time, no checker in the loop: whenever the host sees a
+    metadata or payload flag, the host-visible record must already be the one that flag announces (a record word
+    held back in a device cache while the flag goes through would show as last round's size or sequence number)."""
+    from gpu_harness import GpuRun
+    wl = W.tiny()
+    g = GpuRun(wl, heap=2 << 20, extra_arenas=(2 << 20,))
+    dyn = [i for i, t in enumerate(wl.tensors) if not t.is_static]
+    src = g.extra_t[0].data_ptr()
+    rng = np.random.Generator(np.random.PCG64(77))
+    for seq in range(1, 401):
+        rows = [int(r) for r in rng.integers(1, 513, size=len(dyn))]
+        R.rdev_dyn_reset(g.plan)
+        xs = [R.make_xfer(t, src + k * (1 << 20), R.F32, (r, 256)) for k, (t, r) in enumerate(zip(dyn, rows))]
+        R.rdev_write_batch(g.dev, g.plan, xs, R.ZEROCOPY, seq, g.s)
+        if seq % 2:
+            for t, r in zip(dyn, rows):
+                ok, m = g.wait(t, R.POLL_META | R.POLL_CONSUME, want_meta=True)
+                assert (m.seq, m.bytes, m.dims[0], m.tensor_id, m.meta_flag) == (seq, r * 1024, r, t, seq), (seq, t)
+            R.rdev_read_batch(g.dev, g.plan, [R.make_xfer(t) for t in dyn], seq, g.s)
+        else:
+            R.rdev_read_batch_device(g.dev, g.plan, [R.make_xfer(t) for t in dyn], seq, g.s)
+        off = R.rdev_plan_arena_info(g.plan, g.recv_ids[0])["heap_offset"]
+        for t, r in zip(dyn, rows):
+            ok, m = g.wait(t, R.POLL_CONSUME, want_meta=True)
+            assert (m.seq, m.bytes, m.data_flag, m.dst_offset) == (seq, r * 1024, seq, off), (seq, t)
+            off += r * 1024
+        if seq % 2 == 0:
+            st = R.rdev_recv_status(g.plan)
+            assert st["status"] == R.OK and st["calls_done"] == st["calls_made"]
+    g.close()
+
+
 def test_device_side_receive_many_tensors_mixed_with_host_path():
     """12 dynamic tensors over 3 arenas, odd sizes and element types: the first 4 received through the host path,
     the rest on the device in the same iteration (one heap, allocation order = batch order throughout)."""
