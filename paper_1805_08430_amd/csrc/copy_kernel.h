@@ -43,6 +43,15 @@ struct InlineBatch {
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef v4u v4u_a4 __attribute__((aligned(4)));   // a 16-byte vector at a 4-byte aligned address
 
+// The store of the data mover: a 16-byte streaming store that also writes through (sc1), so that the line does not
+// wait in the L2 for a later write-back.  The compiler's non-temporal store sets "nt" only; there is no builtin for
+// the write-through bit on a 16-byte store, hence the one line of assembly.  Measured on the 553 MB copy: 163.7 us
+// against 167.6 us with the plain non-temporal store (loads: non-temporal is best, further bits change nothing).
+// The s_nop keeps a following write of the data registers clear of the store's operand read.
+__device__ __forceinline__ void store_stream(v4u *p, v4u r) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(r) : "memory");
+}
+
 __device__ __forceinline__ uint32_t funnel(uint32_t lo, uint32_t hi, uint32_t shift_bits) {
     return (uint32_t)((((uint64_t)hi << 32) | lo) >> shift_bits);
 }
@@ -51,9 +60,11 @@ __device__ __forceinline__ uint32_t funnel(uint32_t lo, uint32_t hi, uint32_t sh
 // dst is 16-byte aligned.  src may have any alignment:
 //   src % 16 == 0 : 16-byte loads
 //   src %  4 == 0 : 16-byte loads at 4-byte alignment
-//   otherwise     : five aligned dwords per vector, shifted into place; the
-//                   extra dword always shares a word with a valid source byte,
-//                   so nothing outside the source's pages is touched.
+//   otherwise     : five aligned dwords per vector, shifted into place (four loaded,
+//                   the fifth handed over by the neighbouring lane); the extra
+//                   dword always shares a word with a valid source byte, so
+//                   nothing outside the source's pages is touched.
+// nth must be a multiple of 64 and the lanes of a wave must hold consecutive tid.
 // Streaming (non-temporal) accesses: nothing is reused.
 __device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst,
                                           uint32_t bytes, uint32_t tid, uint32_t nth) {
@@ -63,25 +74,36 @@ __device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src, uint8
     if ((sa & 15) == 0) {
         const v4u *s = (const v4u *)src;
         for (uint32_t i = tid; i < nvec; i += nth)
-            __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
+            store_stream(d + i, __builtin_nontemporal_load(s + i));
     } else if ((sa & 3) == 0) {
         const v4u_a4 *s = (const v4u_a4 *)src;
         for (uint32_t i = tid; i < nvec; i += nth)        // same instruction, streaming as well: measured equal to the aligned case
-            __builtin_nontemporal_store((v4u)__builtin_nontemporal_load(s + i), d + i);
+            store_stream(d + i, (v4u)__builtin_nontemporal_load(s + i));
     } else {
+        // Byte-misaligned source: vector i needs the five aligned dwords that cover it.  Four come with one 16-byte
+        // load; the fifth is the first dword of vector i + 1, which the next lane has just loaded, so it is passed
+        // across the wave instead of being loaded again.  Only a lane whose neighbour holds no vector (the last lane
+        // of the wave, or the last vector) fetches its fifth dword itself.  The wave walks the loop as a whole.
         const uint32_t m = (uint32_t)(sa & 3);
         const uint32_t sh = m * 8;
         const uint32_t *base = (const uint32_t *)(sa - m);
-        for (uint32_t i = tid; i < nvec; i += nth) {
+        const uint32_t lane = tid & 63;
+        for (uint32_t i0 = tid - lane; i0 < nvec; i0 += nth) {          // i0: this wave's first vector, same for all its lanes
+            const uint32_t i = i0 + lane;
+            const bool on = i < nvec;
             const uint32_t *w = base + 4 * (size_t)i;
-            v4u lo = __builtin_nontemporal_load((const v4u_a4 *)w);
-            uint32_t w4 = __builtin_nontemporal_load(w + 4);
-            v4u r;
-            r.x = funnel(lo.x, lo.y, sh);
-            r.y = funnel(lo.y, lo.z, sh);
-            r.z = funnel(lo.z, lo.w, sh);
-            r.w = funnel(lo.w, w4, sh);
-            __builtin_nontemporal_store(r, d + i);
+            v4u lo = {0, 0, 0, 0};
+            if (on) lo = __builtin_nontemporal_load((const v4u_a4 *)w);
+            uint32_t w4 = __shfl_down(lo.x, 1, 64);
+            if (on && (lane == 63 || i + 1 >= nvec)) w4 = __builtin_nontemporal_load(w + 4);
+            if (on) {
+                v4u r;
+                r.x = funnel(lo.x, lo.y, sh);
+                r.y = funnel(lo.y, lo.z, sh);
+                r.z = funnel(lo.z, lo.w, sh);
+                r.w = funnel(lo.w, w4, sh);
+                store_stream(d + i, r);
+            }
         }
     }
     const uint32_t rem = bytes & 15;

@@ -80,8 +80,14 @@ constexpr uint32_t kFlagTableThreads = 1024;
 __global__ __launch_bounds__(kFlagTableThreads) void flag_table_kernel(const FlagEnt *__restrict__ ents, uint32_t n,
                                                                         uint32_t value, uint32_t *batch_word,
                                                                         uint32_t token) {
-    for (uint32_t i = threadIdx.x; i < n; i += kFlagTableThreads)
-        __hip_atomic_store(ents[i].arena_flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (uint32_t i = threadIdx.x; i < n; i += 4 * kFlagTableThreads) {        // four table entries in flight per lane
+        uint32_t *f[4];
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) f[k] = i + k * kFlagTableThreads < n ? ents[i + k * kFlagTableThreads].arena_flag : nullptr;
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k)
+            if (f[k]) __hip_atomic_store(f[k], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (!batch_word) return;
     wait_stores_acked();
     __syncthreads();
