@@ -65,8 +65,9 @@ def parse():
     ap.add_argument("--small-bytes", type=int, default=0)
     ap.add_argument("--flag-groups", type=int, default=0,
                     help="launches per whole-plan transfer, each followed by its tensors' flags (default one)")
-    ap.add_argument("--misalign", action="store_true",
-                    help="vgg16 only: source k starts k mod 16 bytes off a 16-byte boundary (all alignment classes)")
+    ap.add_argument("--misalign", type=int, default=0,
+                    help="vgg16 only: 16 = source k starts k mod 16 bytes off a 16-byte boundary (all alignment "
+                         "classes); 1..15 = every source starts that many bytes off")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-modes", action="store_true", help="skip the untimed comparison with the copying modes")
     ap.add_argument("--mode-steps", type=int, default=60)
@@ -486,7 +487,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     R.lib()
-    wl = W.vgg16(misalign=True) if (a.misalign and a.workload == "vgg16") else {**W.CONFIGS, **W.EXTRA_CONFIGS}[a.workload]()
+    wl = W.vgg16(misalign=True if a.misalign == 16 else a.misalign) if (a.misalign and a.workload == "vgg16") \
+        else {**W.CONFIGS, **W.EXTRA_CONFIGS}[a.workload]()
     payload = wl.payload_bytes
     rotate = a.rotate or max(2, -(-(1 << 30) // max(2 * payload, 1)))
     rotate = min(rotate, 64)

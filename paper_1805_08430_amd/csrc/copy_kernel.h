@@ -92,10 +92,13 @@ __device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src, uint8
             const uint32_t i = i0 + lane;
             const bool on = i < nvec;
             const uint32_t *w = base + 4 * (size_t)i;
+            const bool own5 = on && (lane == 63 || i + 1 >= nvec);
             v4u lo = {0, 0, 0, 0};
+            uint32_t own = 0;
             if (on) lo = __builtin_nontemporal_load((const v4u_a4 *)w);
+            if (own5) own = __builtin_nontemporal_load(w + 4);          // issued before anything waits for `lo`
             uint32_t w4 = __shfl_down(lo.x, 1, 64);
-            if (on && (lane == 63 || i + 1 >= nvec)) w4 = __builtin_nontemporal_load(w + 4);
+            if (own5) w4 = own;
             if (on) {
                 v4u r;
                 r.x = funnel(lo.x, lo.y, sh);

@@ -188,9 +188,10 @@ def alexnet() -> Workload:
                     "8 weight + 8 bias tensors, ungrouped shapes as listed")
 
 
-def vgg16(misalign: bool = False) -> Workload:
+def vgg16(misalign=False) -> Workload:
     """misalign=True: the same tensors, but source k starts k mod 16 bytes off a 16-byte boundary, so that every
-    alignment class of the copy routine (16-byte, 4-byte, byte) is exercised on full-size tensors."""
+    alignment class of the copy routine (16-byte, 4-byte, byte) is exercised on full-size tensors.
+    misalign=n (1..15): every source starts n bytes off a 16-byte boundary."""
     seed = SEED_BASE + 2
     chans = [(3, 64), (64, 64), (64, 128), (128, 128), (128, 256), (256, 256), (256, 256),
              (256, 512), (512, 512), (512, 512), (512, 512), (512, 512), (512, 512)]
@@ -202,7 +203,8 @@ def vgg16(misalign: bool = False) -> Workload:
         shift = 0
         for k, t in enumerate(tensors):
             shift += 16
-            t.src_offset += shift + (k % 16)          # keeps the sources apart and walks through all 16 offsets
+            # keeps the sources apart; walks through all 16 offsets, or applies the one that was asked for
+            t.src_offset += shift + ((k % 16) if misalign is True else int(misalign) % 16)
         sb = [sb[0] + shift + 64]
     return Workload("vgg16", seed, tensors, 1, 8, sb, "normal",
                     "16 weight + 16 bias tensors, tensor i -> receiver arena i mod 8")
