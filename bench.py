@@ -77,6 +77,10 @@ def parse():
     ap.add_argument("--time-every", type=int, default=0,
                     help="time every n-th copy-kernel launch of a set with HIP events (the launch's own start/stop "
                          "events; one costs about 7 us of stream time); 0 = every 2nd in runs under 100 steps, else every 8th")
+    ap.add_argument("--consume-stream", choices=["auto", "own", "delivery"], default="auto",
+                    help="where the receiver's in-arena flag clears travel: a stream of the receiver's own, or the "
+                         "delivery's; auto = own for sets of 256 tensors or more (their clear kernel is long enough "
+                         "to be worth taking off the delivery stream), else the delivery's")
     ap.add_argument("--host-dynamic", action="store_true",
                     help="dynamic tensors: receive through the host (metadata poll, then rdev_read_batch) instead of on the device")
     return ap.parse_args()
@@ -507,6 +511,8 @@ def main():
     dyn_bytes = (sum(b for _, b in sets[0].dyn_variants) / len(sets[0].dyn_variants)) if has_dyn else 0
     torch.cuda.synchronize()
 
+    consume_own = a.consume_stream == "own" or (a.consume_stream == "auto" and len(wl.static_tensors) >= 256)
+
     def spin(fn):
         spins = 0
         while not fn():
@@ -517,10 +523,11 @@ def main():
     def wait_consume(ts, alone=False):
         # rotating sets: the clears travel on the receiver's own stream, off the next delivery's path; one set alone:
         # the next delivery has to wait for the clear anyway, and the delivery's own stream is the cheapest order
-        spin(lambda: R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, s if alone else sr))
+        own = consume_own and not alone
+        spin(lambda: R.rdev_poll(dev, ts.plan, R.ALL_TENSORS, R.POLL_CONSUME, sr if own else s))
         if ts.dyn_variants:
             for t in ts.dyn_ids:
-                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, s2 if alone else sr))
+                spin(lambda: R.rdev_poll(dev, ts.plan, t, R.POLL_CONSUME, sr if own else s2))
 
     seq = 0
 
@@ -605,7 +612,8 @@ def main():
                             + ("metadata write, host poll of the metadata, allocate + pull" if a.host_dynamic else
                                "metadata write, then the receiver's allocate + pull on the GPU without a host poll")
                             + ", on a second stream" if has_dyn else "")
-                           + " + poll/consume of the previous iteration (in-arena clears on the receiver's own stream)"},
+                           + " + poll/consume of the previous iteration (in-arena clears on "
+                           + ("the receiver's own stream)" if consume_own else "the delivery's stream)")},
         "us_per_iteration": round(ms_per_step * 1e3, 2),
         "hbm_gbs_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_frac_per_step": round(algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

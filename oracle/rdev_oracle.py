@@ -38,7 +38,9 @@ that ordering properties (no flag before its payload) can be checked.
 Pins (tests, CPU only): plan invariants + closed-form prefix sums + brute-force
 pairwise disjointness; byte-at-a-time movers on exhaustive tiny inputs; the
 one-aligned-tensor case against numpy slice assignment; RPC modes against the
-zero-copy result; metadata bytes against a hand-assembled fixture; gather
+zero-copy result and against message, fragment and staging buffers rebuilt one
+byte at a time; the place a poll names after an RPC delivery and after a later
+zero-copy delivery; metadata bytes against a hand-assembled fixture; gather
 against nested Python loops.  No function here is unpinned.
 """
 from __future__ import annotations

@@ -102,16 +102,17 @@ struct InlineFlags {
     uint32_t value;
 };
 
-// the same for a few tensors named in the kernel arguments, one host-visible word each, stored once the lane's
-// in-arena store has been acknowledged
-__global__ void flag_inline_kernel(InlineFlags f, uint32_t *mirror) {
+// the same for a few tensors named in the kernel arguments (no table to fetch first: one memory round trip less).
+// With `mirror`: one host-visible word each, stored once the lane's in-arena store has been acknowledged.
+// With `batch_word`: one token for all of them, stored by lane 0 once the wave's stores have been acknowledged.
+__global__ __launch_bounds__(64) void flag_inline_kernel(InlineFlags f, uint32_t *mirror, uint32_t *batch_word,
+                                                         uint32_t token) {
     const uint32_t i = threadIdx.x;
-    if (i >= f.n) return;
-    __hip_atomic_store(f.arena_flag[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (mirror) {
-        wait_stores_acked();
-        __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
+    if (i < f.n) __hip_atomic_store(f.arena_flag[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!mirror && !batch_word) return;
+    wait_stores_acked();                     // one wave: its own wait covers every lane's store
+    if (mirror && i < f.n) __hip_atomic_store(mirror + f.mirror_idx[i], f.value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (batch_word && i == 0) __hip_atomic_store(batch_word, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Dynamic path, sender side: 120 bytes of metadata into the receiver's slot

@@ -123,6 +123,7 @@ struct rdev_plan_s {
     // device tables for the "whole plan" transfer
     DevBuf<Item> d_items, d_subs;
     DevBuf<FlagEnt> d_flags;                         // static tensors, plan order
+    std::vector<uint32_t *> h_flag_ptrs;             // the same in-arena flag addresses, host copy
     uint32_t n_blocks = 0;
 
     // host-visible words: flags[2*i] = completion / payload-complete, flags[2*i+1] = metadata flag
@@ -323,6 +324,15 @@ rdev_status launch_copy_table(const Item *items, const Item *subs, uint32_t n_bl
 rdev_status launch_group_flags(rdev_plan_t *plan, uint32_t g, uint32_t seq, uint32_t token, hipStream_t s) {
     const rdev_plan_s::Group &gr = plan->groups[g];
     if (!gr.n_flags) return RDEV_OK;
+    if (gr.n_flags <= rdev::kFlagInlineMax) {        // few enough to travel in the kernel arguments
+        rdev::InlineFlags f{};
+        f.value = seq;
+        f.n = gr.n_flags;
+        for (uint32_t k = 0; k < gr.n_flags; ++k) f.arena_flag[k] = plan->h_flag_ptrs[gr.first_flag + k];
+        hipLaunchKernelGGL(rdev::flag_inline_kernel, dim3(1), dim3(64), 0, s, f, (uint32_t *)nullptr,
+                           plan->d_batch_view + g, token);
+        return launch_check("flag_inline_kernel");
+    }
     hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(1), dim3(rdev::kFlagTableThreads), 0, s,
                        plan->d_flags.ptr + gr.first_flag, gr.n_flags, seq, plan->d_batch_view + g, token);
     return launch_check("flag_table_kernel");
@@ -409,7 +419,7 @@ rdev_status launch_inline_flags(rdev_plan_t *plan, const std::vector<std::pair<u
             ++i;
         }
         hipLaunchKernelGGL(rdev::flag_inline_kernel, dim3(1), dim3(64), 0, s, f,
-                           with_mirror ? plan->d_flags_view : nullptr);
+                           with_mirror ? plan->d_flags_view : nullptr, (uint32_t *)nullptr, 0u);
         RDEV_TRY(launch_check("flag_inline_kernel"));
     }
     return RDEV_OK;
@@ -674,6 +684,7 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
                 if (e != hipSuccess) return bail(e, "hipMemset(metadata slot)");
             }
         }
+        for (const FlagEnt &f : fe) raw->h_flag_ptrs.push_back(f.arena_flag);
         e = raw->d_flags.upload(fe);
         if (e != hipSuccess) return bail(e, "upload(flag table)");
         if (!fe.empty()) {
@@ -1422,9 +1433,18 @@ rdev_status rdev_poll(rdev_device_t *dev, rdev_plan_t *plan, uint32_t tensor_id,
         if (consume && plan->n_static) {
             for (uint32_t i = 0; i < plan->pl.size(); ++i)
                 if (plan->pl[i].kind == RDEV_STATIC) static_consume(plan, i, toks[i]);
-            hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(1), dim3(rdev::kFlagTableThreads), 0, s,
-                               plan->d_flags.ptr, plan->n_static, 0u, (uint32_t *)nullptr, 0u);
-            RDEV_TRY(launch_check("flag_table_kernel"));
+            if (plan->n_static <= rdev::kFlagInlineMax) {
+                rdev::InlineFlags f{};
+                f.n = plan->n_static;
+                for (uint32_t k = 0; k < plan->n_static; ++k) f.arena_flag[k] = plan->h_flag_ptrs[k];
+                hipLaunchKernelGGL(rdev::flag_inline_kernel, dim3(1), dim3(64), 0, s, f, (uint32_t *)nullptr,
+                                   (uint32_t *)nullptr, 0u);
+                RDEV_TRY(launch_check("flag_inline_kernel"));
+            } else {
+                hipLaunchKernelGGL(rdev::flag_table_kernel, dim3(1), dim3(rdev::kFlagTableThreads), 0, s,
+                                   plan->d_flags.ptr, plan->n_static, 0u, (uint32_t *)nullptr, 0u);
+                RDEV_TRY(launch_check("flag_table_kernel"));
+            }
             RDEV_TRY(after_clear(plan, s));
         }
         return RDEV_OK;
