@@ -79,8 +79,9 @@ def parse():
                          "events; one costs about 7 us of stream time); 0 = every 2nd in runs under 100 steps, else every 8th")
     ap.add_argument("--consume-stream", choices=["auto", "own", "delivery"], default="auto",
                     help="where the receiver's in-arena flag clears travel: a stream of the receiver's own, or the "
-                         "delivery's; auto = own for sets of 256 tensors or more (their clear kernel is long enough "
-                         "to be worth taking off the delivery stream), else the delivery's")
+                         "delivery's; auto = own when an iteration moves 32 MiB or more (the step is bound by the "
+                         "GPU and the clears are worth taking off the delivery stream), else the delivery's (the "
+                         "step is bound by host launches and the extra event costs more than it saves)")
     ap.add_argument("--host-dynamic", action="store_true",
                     help="dynamic tensors: receive through the host (metadata poll, then rdev_read_batch) instead of on the device")
     return ap.parse_args()
@@ -511,7 +512,7 @@ def main():
     dyn_bytes = (sum(b for _, b in sets[0].dyn_variants) / len(sets[0].dyn_variants)) if has_dyn else 0
     torch.cuda.synchronize()
 
-    consume_own = a.consume_stream == "own" or (a.consume_stream == "auto" and len(wl.static_tensors) >= 256)
+    consume_own = a.consume_stream == "own" or (a.consume_stream == "auto" and payload >= (32 << 20))
 
     def spin(fn):
         spins = 0

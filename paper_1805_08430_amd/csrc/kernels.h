@@ -502,61 +502,70 @@ __device__ __forceinline__ uint32_t consume_wait(const uint32_t *flag, uint32_t 
     return seen;
 }
 
-// Reduce 16-byte vectors [v0, v1) of payload (lane i takes v0 + i, v0 + i + stride, ...), plus the up to three
-// trailing words when `tail` is set, and merge the workgroup's result into *out; the workgroup that brings the
-// arrival count to `arrivals_needed` publishes the result.  Call with all kConsumeThreads lanes.
-__device__ __forceinline__ void consume_slice(const uint8_t *payload, uint64_t bytes, uint64_t v0, uint64_t v1,
-                                              uint64_t first, uint64_t stride, bool tail, uint32_t seen,
-                                              uint32_t arrivals_needed, rdev_consume_result *out, uint32_t *s_max,
-                                              uint64_t *s_sum) {
-    const v4u *p = (const v4u *)payload;
-    uint32_t m = kOrdNegInf;
+// A lane's running result over the 32-bit words it has looked at.
+struct ConsumeAcc {
+    uint32_t m = kOrdNegInf;        // ordered key of the largest non-NaN value so far
     uint64_t sum = 0;
-    auto take = [&](uint32_t w) {
+    __device__ __forceinline__ void take(uint32_t w) {
         sum += w;
         if ((w & 0x7FFFFFFFu) <= 0x7F800000u) {         // not a NaN
             const uint32_t o = f2ord(w);
             m = o > m ? o : m;
         }
-    };
+    }
+};
+
+// Lane-local part: 16-byte vectors [v0, v1) of payload (this lane takes v0 + first, v0 + first + stride, ...), plus the
+// up to three trailing words when `tail` is set.  Eight loads in flight per lane: the loop is latency-bound otherwise.
+__device__ __forceinline__ void consume_accumulate(ConsumeAcc &acc, const uint8_t *payload, uint64_t bytes, uint64_t v0,
+                                                   uint64_t v1, uint64_t first, uint64_t stride, bool tail) {
+    const v4u *p = (const v4u *)payload;
     uint64_t i = v0 + first;
-    for (; i + 7 * stride < v1; i += 8 * stride) {      // eight loads in flight per lane: the loop is latency-bound otherwise
+    for (; i + 7 * stride < v1; i += 8 * stride) {
         v4u v[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load(p + i + k * stride);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) { take(v[k].x); take(v[k].y); take(v[k].z); take(v[k].w); }
+        for (int k = 0; k < 8; ++k) { acc.take(v[k].x); acc.take(v[k].y); acc.take(v[k].z); acc.take(v[k].w); }
     }
     for (; i < v1; i += stride) {
         const v4u v = __builtin_nontemporal_load(p + i);
-        take(v.x); take(v.y); take(v.z); take(v.w);
+        acc.take(v.x); acc.take(v.y); acc.take(v.z); acc.take(v.w);
     }
-    if (tail) {                                          // up to three trailing words
+    if (tail) {
         const uint32_t nt = (uint32_t)((bytes & 15) >> 2);
-        if (threadIdx.x < nt) take(((const uint32_t *)payload)[(bytes >> 4) * 4 + threadIdx.x]);
+        if (threadIdx.x < nt) acc.take(((const uint32_t *)payload)[(bytes >> 4) * 4 + threadIdx.x]);
     }
+}
+
+// Workgroup part: fold the lanes' results, merge them into *out and count `arrivals` in; whoever brings the count to
+// `arrivals_needed` publishes the result.  Call with all kConsumeThreads lanes.
+// Everything the workgroups exchange goes through agent-scope atomics, which are performed where all compute dies
+// meet; so no cache write-back or invalidation is needed around the arrival count, only that this lane's two
+// contributions have been performed before it counts itself in.
+__device__ __forceinline__ void consume_flush(ConsumeAcc acc, uint32_t seen, uint32_t arrivals, uint32_t arrivals_needed,
+                                              rdev_consume_result *out, uint32_t *s_max, uint64_t *s_sum) {
+    uint32_t m = acc.m;
+    uint64_t sum = acc.sum;
     for (int off = 32; off > 0; off >>= 1) {
         const uint32_t om = __shfl_down(m, off, 64);
         const uint64_t os = __shfl_down(sum, off, 64);
         m = om > m ? om : m;
         sum += os;
     }
-    __syncthreads();                                     // s_max / s_sum may still be read from an earlier slice
+    __syncthreads();                                     // s_max / s_sum may still be read from an earlier flush
     if ((threadIdx.x & 63) == 0) { s_max[threadIdx.x >> 6] = m; s_sum[threadIdx.x >> 6] = sum; }
     __syncthreads();
     if (threadIdx.x == 0) {
         for (uint32_t w = 1; w < kConsumeThreads / 64; ++w) { m = s_max[w] > m ? s_max[w] : m; sum += s_sum[w]; }
-        // Everything the workgroups exchange goes through agent-scope atomics, which are performed at the point all
-        // compute dies share; so no cache write-back or invalidation is needed around the arrival count, only that
-        // this lane's two contributions have been performed before it counts itself in.
         __hip_atomic_fetch_max((uint32_t *)&out->max, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_fetch_add((unsigned long long *)&out->word_sum, (unsigned long long)sum, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
         wait_stores_acked();
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (prev + 1 == arrivals_needed) {               // last one: publish
+        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + arrivals == arrivals_needed) {        // last one: publish
             const uint32_t key = __hip_atomic_load((uint32_t *)&out->max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ((uint32_t *)&out->max)[0] = ord2f(key);
             out->seen_flag = seen;
@@ -576,15 +585,20 @@ __global__ __launch_bounds__(kConsumeThreads) void consume_reduce_max_kernel(con
         seen = consume_wait(flag, max_spins, &s_seen);
         if (!seen) return;                              // status stays 1: every workgroup leaves
     }
-    consume_slice(payload, bytes, 0, bytes >> 4, (uint64_t)blockIdx.x * kConsumeThreads + threadIdx.x,
-                  (uint64_t)gridDim.x * kConsumeThreads, blockIdx.x == 0, seen, gridDim.x, out, s_max, s_sum);
+    ConsumeAcc acc;
+    consume_accumulate(acc, payload, bytes, 0, bytes >> 4, (uint64_t)blockIdx.x * kConsumeThreads + threadIdx.x,
+                       (uint64_t)gridDim.x * kConsumeThreads, blockIdx.x == 0);
+    consume_flush(acc, seen, 1, gridDim.x, out, s_max, s_sum);
 }
 
 // The same for a list of tensors in one launch.  A tensor is cut into units of kConsumeUnitBytes; workgroup w takes
-// units w, w + grid, ... of the whole list in order, so tensors early in the list are reduced first.  With
-// max_spins > 0 each unit first waits (bounded) for its tensor's in-arena flag, which lets one launch follow a
-// delivery that is still in flight: tensors whose flag is up are reduced while later ones are still moving.
-// A unit whose wait runs out is skipped; its tensor's result keeps status 1.  Every workgroup ends.
+// units w, w + grid, ... of the whole list in order, so tensors early in the list are reduced first.  A workgroup
+// keeps its lanes' results across the units of one tensor and merges them into the tensor's result once, when it
+// moves on to another tensor or runs out of units (merging per unit would queue thousands of atomics on the three
+// words of a large tensor's result).  With max_spins > 0 a workgroup first waits (bounded) for the in-arena flag of
+// each tensor it meets, which lets one launch follow a delivery that is still in flight: tensors whose flag is up are
+// reduced while later ones are still moving.  Units of a tensor whose wait ran out are skipped; its result keeps
+// status 1.  Every workgroup ends.
 constexpr uint32_t kConsumeBatchMax = 32;
 constexpr uint32_t kConsumeUnitBytes = 64 * 1024;
 constexpr uint32_t kConsumeTableMaxBlocks = 256;     // when the kernel may have to wait (waiting workgroups hold wave slots)
@@ -605,23 +619,26 @@ __global__ __launch_bounds__(kConsumeThreads) void consume_table_kernel(ConsumeB
     __shared__ uint32_t s_seen;
     __shared__ uint32_t s_max[kConsumeThreads / 64];
     __shared__ uint64_t s_sum[kConsumeThreads / 64];
-    uint32_t k = 0, waited_k = 0xFFFFFFFFu, seen = 0;
+    uint32_t k = 0, cur = 0xFFFFFFFFu, seen = 0, done = 0;
+    ConsumeAcc acc;
     for (uint32_t u = blockIdx.x; u < b.n_units; u += gridDim.x) {
         while (u >= b.e[k].first_unit + b.e[k].n_units) ++k;          // units ascend, so does the tensor
-        const ConsumeEnt &e = b.e[k];
-        if (b.max_spins) {
-            if (k != waited_k) {                                      // one wait per tensor and workgroup
-                seen = consume_wait(e.flag, b.max_spins, &s_seen);
-                waited_k = k;
-            }
-            if (!seen) continue;
+        if (k != cur) {                                               // on to another tensor
+            if (done) consume_flush(acc, seen, done, b.e[cur].n_units, out + cur, s_max, s_sum);
+            acc = ConsumeAcc();
+            done = 0;
+            cur = k;
+            seen = b.max_spins ? consume_wait(b.e[k].flag, b.max_spins, &s_seen) : 0;
         }
+        if (b.max_spins && !seen) continue;
+        const ConsumeEnt &e = b.e[k];
         const uint32_t j = u - e.first_unit;
         const uint64_t nvec = e.bytes >> 4, per = kConsumeUnitBytes / 16;
         const uint64_t v0 = (uint64_t)j * per, v1 = v0 + per < nvec ? v0 + per : nvec;
-        consume_slice(e.payload, e.bytes, v0, v1, threadIdx.x, kConsumeThreads, j + 1 == e.n_units, seen, e.n_units,
-                      out + k, s_max, s_sum);
+        consume_accumulate(acc, e.payload, e.bytes, v0, v1, threadIdx.x, kConsumeThreads, j + 1 == e.n_units);
+        ++done;
     }
+    if (done) consume_flush(acc, seen, done, b.e[cur].n_units, out + cur, s_max, s_sum);
 }
 
 }  // namespace rdev
