@@ -31,8 +31,11 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for a plain 256 MiB device-to-device copy (profiles/copy_table_kernel_<workload>.md).
 # Valid only for the kernel sources they were taken with: `hash` covers csrc/copy_kernel.h + csrc/copy_table.h.
 TRAFFIC = {
-    "vgg16": {"hash": "c198eecb778ffc8f", "fetch_bytes": 557738622, "write_bytes": 553477556},
-    "inception": {"hash": "c198eecb778ffc8f", "fetch_bytes": 969972660, "write_bytes": 962475665},
+    "vgg16": {"hash": "651043a660fa3f4e", "fetch_bytes": 557744651, "write_bytes": 553430176},
+    "alexnet": {"hash": "651043a660fa3f4e", "fetch_bytes": 251482217, "write_bytes": 249513376},
+    "tiny": {"hash": "651043a660fa3f4e", "fetch_bytes": 3013696, "write_bytes": 2945216},
+    "lstm": {"hash": "651043a660fa3f4e", "fetch_bytes": 232774279, "write_bytes": 230948864},
+    "inception": {"hash": "651043a660fa3f4e", "fetch_bytes": 969978658, "write_bytes": 962396800},
 }
 
 
@@ -309,7 +312,7 @@ def consumer_leg(R, torch, W, dev, wl, opts, s, spin, iters=20):
                     spin(lambda: R.rdev_poll(dev, tg.plan, R.ALL_TENSORS))
                     R.rdev_consume_batch(dev, tg.plan, ids, 0, base, c)
                 else:
-                    R.rdev_consume_batch(dev, tg.plan, ids, 4_000_000, base, c)
+                    R.rdev_consume_batch(dev, tg.plan, ids, 50_000, base, c)
                 cons.synchronize()
                 torch.cuda.synchronize()
                 tt.append((time.perf_counter() - t0) * 1e6)

@@ -382,8 +382,9 @@ typedef struct {
  * section 5.1) for one static tensor whose size is a multiple of 4 bytes.
  * With max_spins > 0 a small grid (64 workgroups at most: waiting workgroups
  * occupy compute units, the cost section 3.5 warns of) first waits until the tensor's
- * in-arena flag is non-zero - acquire loads, at most max_spins of them per
- * workgroup - and then reduces the payload.  max_spins == 0: do not look at the
+ * in-arena flag is non-zero - at most max_spins polls per workgroup, a few
+ * microseconds apart (about 14 us once it has been waiting for a while) - and
+ * then reduces the payload.  max_spins == 0: do not look at the
  * flag at all (the caller has polled it on the host).  out: device pointer, 8-byte
  * aligned; written by kernels on `stream`.  Never waits forever.  A waiting
  * consumer that is enqueued BEFORE the delivery only sees it arrive if the two
@@ -395,8 +396,8 @@ rdev_status rdev_consume_reduce_max(rdev_device_t *dev, rdev_plan_t *plan, uint3
 /* The same consumer for a list of static tensors in one launch per 32 tensors:
  * out[i] belongs to tensor_ids[i].  Tensors are cut into 64 KiB units that the
  * workgroups take in list order, so tensors early in the list are reduced first.
- * With max_spins > 0 every unit first waits (at most max_spins acquire loads) for
- * its tensor's in-arena flag; enqueued on a second stream behind a delivery that
+ * With max_spins > 0 a workgroup first waits (at most max_spins polls, a few
+ * microseconds apart) for the in-arena flag of each tensor it meets; enqueued on a second stream behind a delivery that
  * is still in flight, one launch then consumes each tensor as its flag comes up
  * (with flag_groups > 1 while later groups are still moving).  At most 256
  * workgroups wait at a time; they hold wave slots the copy could use (section

@@ -492,7 +492,10 @@ __device__ __forceinline__ uint32_t consume_wait(const uint32_t *flag, uint32_t 
         for (uint32_t k = 0; k < max_spins; ++k) {
             v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (v) break;
-            __builtin_amdgcn_s_sleep(8);
+            // Back off: hundreds of workgroups poll the same few words, and every poll goes to the one memory channel
+            // that holds the word; polled hard, that channel starves the copy the pollers are waiting for.
+            const uint32_t naps = k < 8 ? 1 : (k < 32 ? 2 : 4);          // about 3.4 us each
+            for (uint32_t j = 0; j < naps; ++j) __builtin_amdgcn_s_sleep(127);
         }
         *s_seen = v;
     }

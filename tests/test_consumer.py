@@ -125,7 +125,7 @@ def test_consumer_and_polling_async_on_gpu():
     for sid, img in zip(o.send_ids, imgs):
         o.image(sid)[:] = img
     big = max(ids, key=lambda t: wl.tensors[t].nbytes)
-    R.rdev_consume_reduce_max(g.dev, g.plan, big, 200_000, base, cons.cuda_stream)
+    R.rdev_consume_reduce_max(g.dev, g.plan, big, 20_000, base, cons.cuda_stream)
     R.rdev_write_batch(g.dev, g.plan, [R.make_xfer(big)], R.ZEROCOPY, 77, g.s)
     O.static_write(o.dev, o.plan, o.sources, 77, tensor_ids=[big])
     cons.synchronize()
@@ -143,7 +143,7 @@ def test_consumer_and_polling_async_on_gpu():
         for sid, img in zip(o.send_ids, imgs):
             o.image(sid)[:] = img
         for k, t in enumerate(watch):
-            R.rdev_consume_reduce_max(g.dev, g.plan, t, 200_000, base + 24 * k, cons.cuda_stream)
+            R.rdev_consume_reduce_max(g.dev, g.plan, t, 20_000, base + 24 * k, cons.cuda_stream)
         R.rdev_write_batch(g.dev, g.plan, [R.make_xfer(t) for t in watch], R.ZEROCOPY, 200 + rnd, g.s)
         O.static_write(o.dev, o.plan, o.sources, 200 + rnd, tensor_ids=watch)
         cons.synchronize()
@@ -213,7 +213,7 @@ def test_consume_batch_one_launch_for_a_list(name, groups):
         for sid, img in zip(o.send_ids, imgs):
             o.image(sid)[:] = img
         R.rdev_write_batch(g.dev, g.plan, None, R.ZEROCOPY, 10 + rnd, g.s)
-        R.rdev_consume_batch(g.dev, g.plan, ids, 2_000_000, base, cons.cuda_stream)
+        R.rdev_consume_batch(g.dev, g.plan, ids, 50_000, base, cons.cuda_stream)
         O.static_write(o.dev, o.plan, o.sources, 10 + rnd)
         cons.synchronize()
         _check_results(_results(res_v, n), o, ids, 10 + rnd)
