@@ -61,7 +61,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "vgg16", "lstm", "inception", "fcn5", "gru"])
+    ap.add_argument("--workload", default="vgg16", choices=["tiny", "alexnet", "vgg16", "lstm", "inception", "fcn5", "gru", "flat"])
     ap.add_argument("--rotate", type=int, default=0,
                     help="number of source/receiver set copies cycled through (0 = enough to exceed 1 GB)")
     ap.add_argument("--chunk-bytes", type=int, default=0)
@@ -71,6 +71,7 @@ def parse():
     ap.add_argument("--misalign", type=int, default=0,
                     help="vgg16 only: 16 = source k starts k mod 16 bytes off a 16-byte boundary (all alignment "
                          "classes); 1..15 = every source starts that many bytes off")
+    ap.add_argument("--flat", default="", help="--workload flat: pieces,receiver arenas (default 1,1), 553430176 bytes in all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-modes", action="store_true", help="skip the untimed comparison with the copying modes")
     ap.add_argument("--mode-steps", type=int, default=60)
@@ -495,8 +496,13 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     R.lib()
-    wl = W.vgg16(misalign=True if a.misalign == 16 else a.misalign) if (a.misalign and a.workload == "vgg16") \
-        else {**W.CONFIGS, **W.EXTRA_CONFIGS}[a.workload]()
+    if a.workload == "flat":
+        pieces, n_recv = (int(v) for v in (a.flat or "1,1").split(","))
+        wl = W.flat(pieces=pieces, n_recv=n_recv)
+    elif a.misalign and a.workload == "vgg16":
+        wl = W.vgg16(misalign=True if a.misalign == 16 else a.misalign)
+    else:
+        wl = {**W.CONFIGS, **W.EXTRA_CONFIGS}[a.workload]()
     payload = wl.payload_bytes
     rotate = a.rotate or max(2, -(-(1 << 30) // max(2 * payload, 1)))
     rotate = min(rotate, 64)

@@ -383,6 +383,16 @@ def gru() -> Workload:
     return Workload("gru", seed, tensors, 1, 1, sb, "normal", "6 tensors")
 
 
-EXTRA_CONFIGS = {"fcn5": fcn5, "gru": gru}
+def flat(nbytes: int = 553430176, n_recv: int = 1, pieces: int = 1) -> Workload:
+    """One sender arena, `pieces` equal fp32 tensors of `nbytes` in total dealt round-robin to `n_recv` receiver
+    arenas: the plain large copy, to tell what a tensor set's structure costs on top of it."""
+    seed = SEED_BASE + 7
+    per = nbytes // pieces // 4
+    tensors = [TensorSpec(f"flat{i}", "f32", (per,), i % n_recv, 0) for i in range(pieces)]
+    sb = _pack_sources(tensors, 1, 256)
+    return Workload("flat", seed, tensors, 1, n_recv, sb, "normal", f"{pieces} tensor(s), {n_recv} receiver arena(s)")
+
+
+EXTRA_CONFIGS = {"fcn5": fcn5, "gru": gru, "flat": flat}
 
 CONFIGS = {"tiny": tiny, "alexnet": alexnet, "vgg16": vgg16, "lstm": lstm, "inception": inception}
