@@ -116,52 +116,21 @@ __device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src, uint8
     }
 }
 
-// The batched transfer.  Workgroup b takes item c = (b % 8) * per_xcd + b / 8: workgroups are handed to the 8 XCDs
-// round-robin (workgroup b runs on XCD b % 8, each XCD with its own L2), so every XCD walks one contiguous eighth of
-// the work instead of every eighth item - measured a few percent faster for a streaming copy.  Tables of fewer than
-// 16 items are walked in order (per_xcd == 0).
-//
-// Where an item's addresses come from: the largest tensors of the batch are described as RANGES in the kernel
-// arguments (first item, item count, source, destination, bytes), and an item inside a range computes its addresses
-// from that; only the remaining items - small tensors, and large ones beyond the kMaxRanges biggest - fetch their
-// 32-byte entry from the table in memory.  A table entry is a dependent load in front of the payload load: about
-// 2.5 us on the 553 MB copy (165.5 us against 163.0 us), which the ranges take away for almost every workgroup.
-constexpr uint32_t kMaxRanges = 24;
-struct TableArgs {
-    const Item *items;                  // item c, in the order the batch was cut (entries inside ranges are not read)
-    const Item *subs;
-    uint32_t n_items;
-    uint32_t per_xcd;                   // ceil(n_items / 8), or 0: workgroup b takes item b
-    uint32_t block_base;                // first workgroup of this launch (a table may take several launches)
-    uint32_t chunk;                     // bytes per item inside a range (the last item of a range may be shorter)
-    uint32_t first[kMaxRanges];         // ranges: first item ...
-    uint32_t count[kMaxRanges];         // ... and item count (0 = unused)
-    const uint8_t *src[kMaxRanges];
-    uint8_t *dst[kMaxRanges];
-    uint64_t bytes[kMaxRanges];
-};
-
-__global__ __launch_bounds__(kBlockThreads) void copy_table_kernel(TableArgs a) {
-    const uint32_t b = blockIdx.x + a.block_base;
-    const uint32_t c = a.per_xcd ? (b % kXcds) * a.per_xcd + b / kXcds : b;
-    if (c >= a.n_items) return;                                  // padding of the XCD order
-    uint32_t hit = kMaxRanges;
-#pragma unroll
-    for (uint32_t k = 0; k < kMaxRanges; ++k)
-        if (c - a.first[k] < a.count[k]) hit = k;                // unsigned: false for c < first
-    if (hit < kMaxRanges) {
-        const uint64_t off = (uint64_t)(c - a.first[hit]) * a.chunk;
-        const uint64_t rem = a.bytes[hit] - off;
-        copy_span(a.src[hit] + off, a.dst[hit] + off, rem < a.chunk ? (uint32_t)rem : a.chunk, threadIdx.x, kBlockThreads);
-        return;
-    }
-    const Item it = a.items[c];
+// The batched transfer: block b takes items[b].  The entry is a load that no other workgroup has made, so it comes
+// from HBM in front of the payload load; on the 553 MB copy that is worth about 2.5 us (165.5 us with the dependent
+// load, 163.0 us with addresses computed from the workgroup number).  Describing the largest tensors as ranges that
+// a workgroup searches instead - in the kernel arguments, or in one small device record shared by all workgroups -
+// was measured too and is slower than the table (186 us and 178 us): three scalar loads in a row in front of every
+// workgroup's first payload load cost more than the one load they save.
+__global__ __launch_bounds__(kBlockThreads) void copy_table_kernel(const Item *__restrict__ items,
+                                                                    const Item *__restrict__ subs) {
+    const Item it = items[blockIdx.x];
     if (it.n_sub == 0) {
         copy_span(it.src, it.dst, it.bytes, threadIdx.x, kBlockThreads);
     } else {
         const uint32_t wave = threadIdx.x >> 6;
         if (wave < it.n_sub) {
-            const Item s = a.subs[it.sub_first + wave];
+            const Item s = subs[it.sub_first + wave];
             copy_span(s.src, s.dst, s.bytes, threadIdx.x & 63, 64);
         }
     }

@@ -21,9 +21,6 @@ using rdev::Item;
 using rdev::cut_items;
 using rdev::flush_small;
 using rdev::xcd_order;
-using rdev::RangeCand;
-using rdev::TableArgs;
-using rdev::make_table_args;
 
 namespace {
 
@@ -135,10 +132,7 @@ struct rdev_plan_s {
     // last one completed; a static tensor is ready when that token differs from the one it consumed
     // With flag_groups = G the static tensors (plan order) form G consecutive groups of about equal bytes;
     // group g has its own launch, its own slice of the flag table and its own token word h_batch[g].
-    struct Group {
-        uint32_t n_blocks = 0, first_flag = 0, n_flags = 0;
-        TableArgs table{};                           // launch description of the group's slice of d_items
-    };
+    struct Group { uint32_t first_block = 0, n_blocks = 0, first_flag = 0, n_flags = 0; };
     std::vector<Group> groups;
     std::vector<uint32_t> group_of;                  // per index (static tensors)
     uint32_t *h_batch = nullptr, *d_batch_view = nullptr;
@@ -187,8 +181,7 @@ struct rdev_plan_s {
     DevBuf<rdev_frag> d_frags;                       // fragmented messages: one header per fragment
     DevBuf<uint8_t *> d_frag_send;
     uint32_t n_frags = 0;
-    uint32_t n_pack_blocks = 0, n_stage_blocks = 0, n_unstage_blocks = 0, n_unpack_blocks = 0;
-    TableArgs pack_table{}, stage_table{}, unstage_table{};
+    uint32_t n_pack_blocks = 0, n_stage_blocks = 0, n_unpack_blocks = 0;
 };
 
 struct rdev_tracer_s {
@@ -318,11 +311,10 @@ rdev_status after_clear(rdev_plan_t *plan, hipStream_t s) {
 }
 
 // one table of work items, in as many launches as the per-launch limit asks for (workgroups are independent)
-rdev_status launch_copy_table(TableArgs t, uint32_t n_blocks, hipStream_t s, const char *what) {
+rdev_status launch_copy_table(const Item *items, const Item *subs, uint32_t n_blocks, hipStream_t s, const char *what) {
     for (uint32_t first = 0; first < n_blocks; first += kMaxBlocksPerLaunch) {
         const uint32_t n = std::min(kMaxBlocksPerLaunch, n_blocks - first);
-        t.block_base = first;
-        hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(n), dim3(rdev::kBlockThreads), 0, s, t);
+        hipLaunchKernelGGL(rdev::copy_table_kernel, dim3(n), dim3(rdev::kBlockThreads), 0, s, items + first, subs);
         RDEV_TRY(launch_check(what));
     }
     return RDEV_OK;
@@ -750,32 +742,27 @@ rdev_status rdev_plan_bind_sources(rdev_plan_t *plan, const void *const *src_ptr
     }
     // descriptor table (section 3.4: the sender keeps each destination address with the sending node)
     std::vector<Item> items, subs;
-    std::vector<size_t> first_item(plan->groups.size());
     for (uint32_t g = 0; g < plan->groups.size(); ++g) {
         std::vector<Item> gi, pending;
-        std::vector<RangeCand> cands;
         for (uint32_t i = 0; i < n; ++i) {
             const rdev_placement &p = plan->pl[i];
             if (p.kind != RDEV_STATIC || !locs[i].bound || plan->group_of[i] != g) continue;
             const uint8_t *s = plan->dev->arenas[locs[i].arena].base + locs[i].offset;
             cut_items(s, arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, i, plan->opts.chunk_bytes,
-                      plan->opts.small_bytes, gi, subs, pending, &cands);
+                      plan->opts.small_bytes, gi, subs, pending);
         }
         flush_small(gi, subs, pending);
-        if (gi.size() > 0xfffffff0ull) return fail(RDEV_E_INVAL, "too many work items; raise chunk_bytes");
-        first_item[g] = items.size();
-        plan->groups[g].table = make_table_args(gi.size(), (uint32_t)plan->opts.chunk_bytes, cands, 0, &plan->groups[g].n_blocks);
+        xcd_order(gi);
+        plan->groups[g].first_block = (uint32_t)items.size();
+        plan->groups[g].n_blocks = (uint32_t)gi.size();
         items.insert(items.end(), gi.begin(), gi.end());
     }
+    if (items.size() > 0xffffffffull) return fail(RDEV_E_INVAL, "too many work items; raise chunk_bytes");
     if (plan->dev->gpu()) {
         HIP_TRY(hipSetDevice(plan->dev->hip_device));
         HIP_TRY(hipDeviceSynchronize());          // nothing may still read the old tables
         HIP_TRY(plan->d_items.upload(items));
         HIP_TRY(plan->d_subs.upload(subs));
-    }
-    for (uint32_t g = 0; g < plan->groups.size(); ++g) {
-        plan->groups[g].table.items = plan->d_items.ptr + first_item[g];
-        plan->groups[g].table.subs = plan->d_subs.ptr;
     }
     plan->n_blocks = (uint32_t)items.size();
     plan->src = std::move(locs);
@@ -810,7 +797,6 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
     uint8_t *rb = plan->have_recv ? dev->arenas[plan->recv_buf.arena_id].base + plan->recv_buf.offset : nullptr;
 
     std::vector<Item> pack, pack_s, stage, stage_s, unstage, unstage_s, pend_a, pend_b, pend_c;
-    std::vector<RangeCand> pack_c, stage_c, unstage_c;
     std::vector<rdev::UItem> us, us_s, ur, ur_s, upend_s, upend_r;
     std::vector<rdev_meta> headers;
     std::vector<uint8_t *> msg_send, msg_recv, frag_send;
@@ -854,7 +840,7 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
         plan->rpc_slot[i] = slot;
         plan->rpc_rel[i] = plan->heap_need[slot];
         if (!F) {
-            cut_items(src, sb + mptr + RDEV_META_BYTES, p.bytes, i, chunk, small, pack, pack_s, pend_a, &pack_c);
+            cut_items(src, sb + mptr + RDEV_META_BYTES, p.bytes, i, chunk, small, pack, pack_s, pend_a);
             push_unpack(us, us_s, upend_s, sb + mptr, plan->rpc_rel[i], slot, p.bytes);
             if (rb) push_unpack(ur, ur_s, upend_r, rb + mptr, plan->rpc_rel[i], slot, p.bytes);
             mptr += RDEV_META_BYTES + ((p.bytes + 15) & ~(uint64_t)15);
@@ -866,7 +852,7 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
                 const uint64_t off = k * F, fb = std::min<uint64_t>(F, p.bytes - off);
                 frags.push_back(rdev_frag{p.tensor_id, 0, (uint32_t)k, (uint32_t)nfrag, off, (uint32_t)fb, 0});
                 frag_send.push_back(sb + mptr);
-                cut_items(src + off, sb + mptr + sizeof(rdev_frag), fb, i, chunk, small, pack, pack_s, pend_a, &pack_c);
+                cut_items(src + off, sb + mptr + sizeof(rdev_frag), fb, i, chunk, small, pack, pack_s, pend_a);
                 push_unpack(us, us_s, upend_s, sb + mptr, plan->rpc_rel[i] + off, slot | rdev::kFragBit, fb);
                 if (rb) push_unpack(ur, ur_s, upend_r, rb + mptr, plan->rpc_rel[i] + off, slot | rdev::kFragBit, fb);
                 mptr += sizeof(rdev_frag) + ((fb + 15) & ~(uint64_t)15);
@@ -875,9 +861,8 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
         plan->heap_need[slot] += (p.bytes + A - 1) & ~(A - 1);
         // staging
         plan->stage_end = std::max(plan->stage_end, sptr + p.bytes);
-        cut_items(src, sb + sptr, p.bytes, i, chunk, small, stage, stage_s, pend_b, &stage_c);
-        cut_items(sb + sptr, arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, i, chunk, small, unstage, unstage_s, pend_c,
-                  &unstage_c);
+        cut_items(src, sb + sptr, p.bytes, i, chunk, small, stage, stage_s, pend_b);
+        cut_items(sb + sptr, arena_ptr(plan, p.dst_arena, p.data_offset), p.bytes, i, chunk, small, unstage, unstage_s, pend_c);
         sptr += (p.bytes + A - 1) & ~(A - 1);
     }
     flush_small(pack, pack_s, pend_a);
@@ -892,11 +877,9 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
         ur_s.insert(ur_s.end(), upend_r.begin(), upend_r.end());
     }
     plan->msg_total = mptr;
-    if (std::max({pack.size(), stage.size(), unstage.size()}) > 0xfffffff0ull)
-        return fail(RDEV_E_INVAL, "too many work items; raise chunk_bytes");
-    plan->pack_table = make_table_args(pack.size(), (uint32_t)chunk, pack_c, 0, &plan->n_pack_blocks);
-    plan->stage_table = make_table_args(stage.size(), (uint32_t)chunk, stage_c, 0, &plan->n_stage_blocks);
-    plan->unstage_table = make_table_args(unstage.size(), (uint32_t)chunk, unstage_c, 0, &plan->n_unstage_blocks);
+    xcd_order(pack);
+    xcd_order(stage);
+    xcd_order(unstage);
     xcd_order(us);
     xcd_order(ur);
     HIP_TRY(hipSetDevice(dev->hip_device));
@@ -917,12 +900,8 @@ rdev_status build_copy_tables(rdev_plan_t *plan) {
     HIP_TRY(plan->d_frags.upload(frags));
     HIP_TRY(plan->d_frag_send.upload(frag_send));
     plan->n_frags = (uint32_t)frags.size();
-    plan->pack_table.items = plan->d_pack_items.ptr;
-    plan->pack_table.subs = plan->d_pack_subs.ptr;
-    plan->stage_table.items = plan->d_stage_items.ptr;
-    plan->stage_table.subs = plan->d_stage_subs.ptr;
-    plan->unstage_table.items = plan->d_unstage_items.ptr;
-    plan->unstage_table.subs = plan->d_unstage_subs.ptr;
+    plan->n_pack_blocks = (uint32_t)pack.size();
+    plan->n_stage_blocks = (uint32_t)stage.size();
     plan->n_unpack_blocks = (uint32_t)us.size();
     plan->copy_tables = true;
     return RDEV_OK;
@@ -949,8 +928,10 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
         if (plan->n_static) token = next_token(plan, seq);
         std::fill(plan->rpc_valid.begin(), plan->rpc_valid.end(), 0);
         if (plan->n_stage_blocks) {
-            RDEV_TRY(launch_copy_table(plan->stage_table, plan->n_stage_blocks, s, "copy_table_kernel(stage)"));
-            RDEV_TRY(launch_copy_table(plan->unstage_table, plan->n_unstage_blocks, s, "copy_table_kernel(write)"));
+            RDEV_TRY(launch_copy_table(plan->d_stage_items.ptr, plan->d_stage_subs.ptr, plan->n_stage_blocks, s,
+                                       "copy_table_kernel(stage)"));
+            RDEV_TRY(launch_copy_table(plan->d_unstage_items.ptr, plan->d_unstage_subs.ptr, plan->n_stage_blocks, s,
+                                       "copy_table_kernel(write)"));
         }
         if (plan->n_static) {
             for (uint32_t g = 0; g < plan->groups.size(); ++g) RDEV_TRY(launch_group_flags(plan, g, seq, token, s));
@@ -983,7 +964,8 @@ rdev_status write_copy_mode(rdev_plan_t *plan, uint32_t mode, uint32_t seq, hipS
             RDEV_TRY(launch_check("rpc_frag_header_kernel"));
         }
         if (plan->n_pack_blocks) {
-            RDEV_TRY(launch_copy_table(plan->pack_table, plan->n_pack_blocks, s, "copy_table_kernel(pack)"));
+            RDEV_TRY(launch_copy_table(plan->d_pack_items.ptr, plan->d_pack_subs.ptr, plan->n_pack_blocks, s,
+                                       "copy_table_kernel(pack)"));
         }
         if (wire) {
             uint8_t *sb = plan->dev->arenas[plan->send_buf.arena_id].base + plan->send_buf.offset;
@@ -1074,12 +1056,14 @@ static rdev_status write_static_all(rdev_plan_t *plan, uint32_t seq, hipStream_t
                 // the launch carries its own start and stop events: they take the kernel's begin and end times,
                 // with no marker packets of their own in the stream
                 hipExtLaunchKernelGGL(rdev::copy_table_kernel, dim3(gr.n_blocks), dim3(rdev::kBlockThreads), 0, s,
-                                      plan->ev_start[plan->ev_used], plan->ev_stop[plan->ev_used], 0, gr.table);
+                                      plan->ev_start[plan->ev_used], plan->ev_stop[plan->ev_used], 0,
+                                      (const Item *)(plan->d_items.ptr + gr.first_block), (const Item *)plan->d_subs.ptr);
                 RDEV_TRY(launch_check("copy_table_kernel"));
                 plan->ev_used++;
             } else {
                 if (timed) HIP_TRY(hipEventRecord(plan->ev_start[plan->ev_used], s));
-                RDEV_TRY(launch_copy_table(gr.table, gr.n_blocks, s, "copy_table_kernel"));
+                RDEV_TRY(launch_copy_table(plan->d_items.ptr + gr.first_block, plan->d_subs.ptr, gr.n_blocks, s,
+                                           "copy_table_kernel"));
                 if (timed) HIP_TRY(hipEventRecord(plan->ev_stop[plan->ev_used++], s));
             }
         }
