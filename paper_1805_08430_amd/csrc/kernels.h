@@ -259,30 +259,41 @@ __device__ __forceinline__ void recv_layout(const RecvBatch &b, const ArenaEnt *
     __syncthreads();
 }
 
-// pull: workgroups stride over the chunks of all payloads of the batch
-__global__ __launch_bounds__(kBlockThreads) void recv_pull_kernel(RecvBatch b, const ArenaEnt *__restrict__ arenas,
-                                                                   const HeapWord *__restrict__ heap) {
+// The receive in one launch.  Every workgroup works the layout out, pulls its share of the chunks (striding over the
+// chunks of all payloads of the batch), waits until its stores are acknowledged and then counts itself in; the
+// workgroup that arrives last finds every payload byte in place and does what follows the pull: record the offsets,
+// consume the metadata flags, move the heap words, raise payload-complete, and tell the host how the batch went
+// (status[0] = code, [1] = entry it refers to, [2] = call id, stored last).  The count carries, in its upper half,
+// how many workgroups found the batch in order: if a record changed under the kernel (a sender still writing - a
+// misuse), some did and some did not, and nothing is published.  *arrivals is zero between launches: the last
+// workgroup clears it, so launches on one plan must not overlap (they would race on the heap words as well).
+__global__ __launch_bounds__(kBlockThreads) void recv_kernel(RecvBatch b, const ArenaEnt *__restrict__ arenas, HeapWord *heap,
+                                                              uint32_t *arrivals, uint32_t *mirror_flags, rdev_meta *mirror_meta,
+                                                              uint32_t *status) {
     __shared__ RecvLayout L;
-    recv_layout(b, arenas, heap, L);
-    if (L.status != RDEV_OK) return;
-    const uint64_t total = L.first_chunk[b.n];
-    for (uint64_t c = blockIdx.x; c < total; c += gridDim.x) {
-        uint32_t k = 0;
-        while (c >= L.first_chunk[k + 1]) ++k;
-        const uint64_t off = (c - L.first_chunk[k]) * b.chunk;
-        const uint64_t rem = L.bytes[k] - off;
-        copy_span(L.src[k] + off, L.dst[k] + off, rem < b.chunk ? (uint32_t)rem : b.chunk, threadIdx.x, kBlockThreads);
-    }
-}
-
-// behind the pull: record the offsets, consume the metadata flags, move the heap pointers, raise payload-complete;
-// and tell the host how the batch went (status[0] = code, [1] = entry it refers to, [2] = call id, stored last)
-__global__ __launch_bounds__(64) void recv_post_kernel(RecvBatch b, const ArenaEnt *__restrict__ arenas, HeapWord *heap,
-                                                        uint32_t *mirror_flags, rdev_meta *mirror_meta, uint32_t *status) {
-    __shared__ RecvLayout L;
+    __shared__ uint32_t s_seen;
     recv_layout(b, arenas, heap, L);
     const uint32_t t = threadIdx.x;
-    if (L.status == RDEV_OK && t < b.n) {
+    const bool ok = L.status == RDEV_OK;
+    if (ok) {
+        const uint64_t total = L.first_chunk[b.n];
+        for (uint64_t c = blockIdx.x; c < total; c += gridDim.x) {
+            uint32_t k = 0;
+            while (c >= L.first_chunk[k + 1]) ++k;
+            const uint64_t off = (c - L.first_chunk[k]) * b.chunk;
+            const uint64_t rem = L.bytes[k] - off;
+            copy_span(L.src[k] + off, L.dst[k] + off, rem < b.chunk ? (uint32_t)rem : b.chunk, t, kBlockThreads);
+        }
+    }
+    wait_stores_acked();                                                 // every wave: its payload stores have landed
+    __syncthreads();
+    if (t == 0) s_seen = __hip_atomic_fetch_add(arrivals, ok ? 0x10001u : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t seen = s_seen;
+    if ((seen & 0xffffu) != gridDim.x - 1) return;                       // somebody else arrives later
+    const uint32_t n_ok = (seen >> 16) + (ok ? 1u : 0u);
+    const bool publish = ok && n_ok == gridDim.x;
+    if (publish && t < b.n) {
         uint8_t *slot = b.e[t].slot;
         store_through((uint64_t *)(slot + 88), L.dst_offset[t]);
         store_host((uint64_t *)&mirror_meta[b.e[t].meta_idx].dst_offset, L.dst_offset[t]);
@@ -300,7 +311,9 @@ __global__ __launch_bounds__(64) void recv_post_kernel(RecvBatch b, const ArenaE
         store_host(mirror_flags + b.e[t].flag_idx, b.seq);
     }
     if (t == 0) {
-        store_host(status, (uint32_t)L.status);
+        store_through(arrivals, 0u);
+        const bool mixed = n_ok != 0 && n_ok != gridDim.x;               // the records changed while the kernel ran
+        store_host(status, (uint32_t)(mixed ? RDEV_NOT_READY : L.status));
         store_host(status + 1, L.bad);
         wait_stores_acked();
         store_host(status + 2, b.call_id);

@@ -148,6 +148,7 @@ struct rdev_plan_s {
 
     // receives that take their sizes on the device (rdev_read_batch_device)
     DevBuf<rdev::HeapWord> d_heap;                   // one bump pointer per destination arena, in map order
+    DevBuf<uint32_t> d_recv_arrivals;                // workgroups of the running receive kernel that are done; 0 between launches
     std::map<uint32_t, uint32_t> heap_word_of;       // destination arena -> index in d_heap
     uint32_t heap_epoch = 1;                         // iteration number; rdev_dyn_reset starts the next one
     bool heap_on_device = false;                     // this iteration's allocations are known to the device only
@@ -664,6 +665,8 @@ rdev_status rdev_plan(rdev_device_t *dev, const rdev_tensor_desc *t, uint32_t n,
             for (auto &kv : raw->arenas) raw->heap_word_of[kv.first] = w++;
             e = raw->d_heap.upload(std::vector<rdev::HeapWord>(std::max<size_t>(w, 1), rdev::HeapWord{0, 0, 0}));
             if (e != hipSuccess) return bail(e, "upload(heap words)");
+            e = raw->d_recv_arrivals.upload(std::vector<uint32_t>(1, 0u));
+            if (e != hipSuccess) return bail(e, "upload(receive arrival count)");
         }
         raw->consumed_token.assign(n, 0);
         const size_t nmeta = std::max<size_t>(raw->n_dyn, 1);
@@ -1392,11 +1395,9 @@ rdev_status rdev_read_batch_device(rdev_device_t *dev, rdev_plan_t *plan, const 
         // (idle workgroups still cost a layout pass each and take wave slots from whatever else is running).
         const uint64_t want = (hinted ? hint : room) / plan->opts.chunk_bytes + b.n;
         const uint32_t grid = (uint32_t)std::min<uint64_t>(want, hinted ? rdev::kRecvMaxBlocks : rdev::kRecvBlocksNoHint);
-        hipLaunchKernelGGL(rdev::recv_pull_kernel, dim3(grid), dim3(rdev::kBlockThreads), 0, s, b, dev->d_arenas, plan->d_heap.ptr);
-        RDEV_TRY(launch_check("recv_pull_kernel"));
-        hipLaunchKernelGGL(rdev::recv_post_kernel, dim3(1), dim3(64), 0, s, b, dev->d_arenas, plan->d_heap.ptr,
-                           plan->d_flags_view, plan->d_meta_view, plan->d_status_view);
-        RDEV_TRY(launch_check("recv_post_kernel"));
+        hipLaunchKernelGGL(rdev::recv_kernel, dim3(grid), dim3(rdev::kBlockThreads), 0, s, b, dev->d_arenas, plan->d_heap.ptr,
+                           plan->d_recv_arrivals.ptr, plan->d_flags_view, plan->d_meta_view, plan->d_status_view);
+        RDEV_TRY(launch_check("recv_kernel"));
         plan->heap_on_device = true;
     }
     return RDEV_OK;
