@@ -31,11 +31,11 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for a plain 256 MiB device-to-device copy (profiles/copy_table_kernel_<workload>.md).
 # Valid only for the kernel sources they were taken with: `hash` covers csrc/copy_kernel.h + csrc/copy_table.h.
 TRAFFIC = {
-    "vgg16": {"hash": "651043a660fa3f4e", "fetch_bytes": 557744651, "write_bytes": 553430176},
-    "alexnet": {"hash": "651043a660fa3f4e", "fetch_bytes": 251482217, "write_bytes": 249513376},
-    "tiny": {"hash": "651043a660fa3f4e", "fetch_bytes": 3013696, "write_bytes": 2945216},
-    "lstm": {"hash": "651043a660fa3f4e", "fetch_bytes": 232774279, "write_bytes": 230948864},
-    "inception": {"hash": "651043a660fa3f4e", "fetch_bytes": 969978658, "write_bytes": 962396800},
+    "vgg16": {"hash": "805ac29d6b5f4fc3", "fetch_bytes": 557744701, "write_bytes": 553430176},
+    "alexnet": {"hash": "805ac29d6b5f4fc3", "fetch_bytes": 251482261, "write_bytes": 249513376},
+    "tiny": {"hash": "805ac29d6b5f4fc3", "fetch_bytes": 3013694, "write_bytes": 2945216},
+    "lstm": {"hash": "805ac29d6b5f4fc3", "fetch_bytes": 232774248, "write_bytes": 230948864},
+    "inception": {"hash": "805ac29d6b5f4fc3", "fetch_bytes": 969978559, "write_bytes": 962396800},
 }
 
 
