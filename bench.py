@@ -302,7 +302,7 @@ def consumer_leg(R, torch, W, dev, wl, opts, s, spin, iters=20):
         images = W.fill_sources(wl, 0)
         tg = TransferSet(R, torch, W, dev, wl, images, dict(opts, flag_groups=G))
         del images
-        for how in ("after_host_poll", "waiting_on_device"):
+        for how in ("after_host_poll", "waiting_on_device", "same_stream_behind_the_write"):
             tt = []
             for it in range(iters + 2):
                 torch.cuda.synchronize()
@@ -312,6 +312,8 @@ def consumer_leg(R, torch, W, dev, wl, opts, s, spin, iters=20):
                 if how == "after_host_poll":
                     spin(lambda: R.rdev_poll(dev, tg.plan, R.ALL_TENSORS))
                     R.rdev_consume_batch(dev, tg.plan, ids, 0, base, c)
+                elif how == "same_stream_behind_the_write":      # stream order instead of flags: no wait at all
+                    R.rdev_consume_batch(dev, tg.plan, ids, 0, base, s)
                 else:
                     R.rdev_consume_batch(dev, tg.plan, ids, 50_000, base, c)
                 cons.synchronize()

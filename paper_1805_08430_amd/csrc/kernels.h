@@ -472,9 +472,14 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const int64_t *__restr
 
 // ---- receiver-side consumer (sections 4, 5.1) ----
 
-constexpr uint32_t kConsumeThreads = 256;
+// Launch shape: 1024-lane workgroups that stay and stride over the payload, four 16-byte loads in flight per lane,
+// two workgroups per compute unit at most.  Read-only 553 MB this way runs at 83 % of HBM peak; 256-lane workgroups
+// reach 78 % with 512 of them and 68 % with 2048, and a fresh workgroup per 64 KiB (whose two atomics per workgroup
+// then dominate) 32 %.  The arithmetic is free beside the loads (the same loop with one xor per word takes as long).
+constexpr uint32_t kConsumeThreads = 1024;
+constexpr uint32_t kConsumeInFlight = 2;
 constexpr uint32_t kConsumeMaxBlocks = 64;         // when the kernel waits for the flag on the device
-constexpr uint32_t kConsumeMaxBlocksNoWait = 2048; // when the host has seen the flag already
+constexpr uint32_t kConsumeMaxBlocksNoWait = 512;  // when the host has seen the flag already
 
 // order-preserving map of non-NaN floats to unsigned (and -0 < +0)
 __device__ __forceinline__ uint32_t f2ord(uint32_t bits) { return bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u); }
@@ -495,9 +500,11 @@ __global__ void consume_init_kernel(rdev_consume_result *out, uint32_t n) {
 }
 
 // One workgroup's wait for a tensor's in-arena flag: at most max_spins loads by one lane (agent scope, relaxed: they
-// go past the caches and cost no invalidation each), the answer shared with the others; once the flag is up every
-// wave makes ONE acquire, so that none of the payload is served from lines an earlier iteration left in the caches.
-// Returns the flag value seen, 0 = gave up.
+// go past the caches and cost no invalidation each), the answer shared with the others.  Once the flag is up the
+// polling wave makes ONE acquire before the others are let go, so that none of the payload is served from lines an
+// earlier iteration left in the caches: the vector cache belongs to the compute unit and the L2 to the die, so one
+// wave's invalidation serves the whole workgroup (an acquire in each of the sixteen waves made the waiting consumer
+// 40 % slower).  Returns the flag value seen, 0 = gave up.
 __device__ __forceinline__ uint32_t consume_wait(const uint32_t *flag, uint32_t max_spins, uint32_t *s_seen) {
     __syncthreads();                                    // s_seen may still be read from an earlier wait
     if (threadIdx.x == 0) {
@@ -511,11 +518,13 @@ __device__ __forceinline__ uint32_t consume_wait(const uint32_t *flag, uint32_t 
             for (uint32_t j = 0; j < naps; ++j) __builtin_amdgcn_s_sleep(127);
         }
         *s_seen = v;
+        if (v) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            wait_stores_acked();                        // the invalidation has been performed before anyone goes on
+        }
     }
     __syncthreads();
-    const uint32_t seen = *s_seen;
-    if (seen) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    return seen;
+    return *s_seen;
 }
 
 // A lane's running result over the 32-bit words it has looked at.
@@ -524,28 +533,39 @@ struct ConsumeAcc {
     uint64_t sum = 0;
     __device__ __forceinline__ void take(uint32_t w) {
         sum += w;
-        if ((w & 0x7FFFFFFFu) <= 0x7F800000u) {         // not a NaN
-            const uint32_t o = f2ord(w);
-            m = o > m ? o : m;
-        }
+        // NaNs drop out by their keys: those of positive NaNs lie above the key of +inf and are replaced by 0, those of
+        // negative NaNs lie below the key of -inf, which m starts from
+        uint32_t o = f2ord(w);
+        o = o > 0xFF800000u ? 0u : o;
+        m = o > m ? o : m;
     }
 };
 
-// Lane-local part: 16-byte vectors [v0, v1) of payload (this lane takes v0 + first, v0 + first + stride, ...), plus the
-// up to three trailing words when `tail` is set.  Eight loads in flight per lane: the loop is latency-bound otherwise.
+// Lane-local part: the 16-byte vectors [v0, v1) of payload, taken by the kConsumeThreads lanes of the workgroup in
+// rounds of `stride` vectors (lane l takes v0 + l, v0 + l + stride, ...), plus the up to three trailing words when
+// `tail` is set.  v0, v1 and stride are the same for every lane.  kConsumeInFlight loads are in flight per lane (the
+// loop is latency-bound otherwise); as long as a whole round lies inside the range the addresses are a uniform base
+// plus a 32-bit lane offset, which keeps the kernel at the register count of the copy kernel - a waiting consumer
+// whose waves need a different amount of registers than the copy's leaves holes in the register files that no copy
+// workgroup fits into, and a copy that is running when such a consumer arrives all but stops until it leaves.
 __device__ __forceinline__ void consume_accumulate(ConsumeAcc &acc, const uint8_t *payload, uint64_t bytes, uint64_t v0,
-                                                   uint64_t v1, uint64_t first, uint64_t stride, bool tail) {
-    const v4u *p = (const v4u *)payload;
-    uint64_t i = v0 + first;
-    for (; i + 7 * stride < v1; i += 8 * stride) {
-        v4u v[8];
+                                                   uint64_t v1, uint64_t stride, bool tail) {
+    constexpr uint32_t K = kConsumeInFlight;
+    const uint32_t lane_off = threadIdx.x * 16u;
+    uint64_t iu = v0;
+    for (; iu + (K - 1) * stride + kConsumeThreads <= v1; iu += K * stride) {
+        const uint8_t *q = payload + iu * 16;                            // uniform
+        v4u v[K];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load(p + i + k * stride);
+        for (uint32_t k = 0; k < K; ++k) v[k] = __builtin_nontemporal_load((const v4u *)(q + k * stride * 16 + lane_off));
 #pragma unroll
-        for (int k = 0; k < 8; ++k) { acc.take(v[k].x); acc.take(v[k].y); acc.take(v[k].z); acc.take(v[k].w); }
+        for (uint32_t k = 0; k < K; ++k) {
+            acc.take(v[k].x); acc.take(v[k].y); acc.take(v[k].z); acc.take(v[k].w);
+            __builtin_amdgcn_sched_barrier(0);           // one vector at a time: interleaving all sixteen words costs 30 registers
+        }
     }
-    for (; i < v1; i += stride) {
-        const v4u v = __builtin_nontemporal_load(p + i);
+    for (uint64_t i = iu + threadIdx.x; i < v1; i += stride) {
+        const v4u v = __builtin_nontemporal_load((const v4u *)payload + i);
         acc.take(v.x); acc.take(v.y); acc.take(v.z); acc.take(v.w);
     }
     if (tail) {
@@ -554,34 +574,52 @@ __device__ __forceinline__ void consume_accumulate(ConsumeAcc &acc, const uint8_
     }
 }
 
-// Workgroup part: fold the lanes' results, merge them into *out and count `arrivals` in; whoever brings the count to
-// `arrivals_needed` publishes the result.  Call with all kConsumeThreads lanes.
-// Everything the workgroups exchange goes through agent-scope atomics, which are performed where all compute dies
-// meet; so no cache write-back or invalidation is needed around the arrival count, only that this lane's two
-// contributions have been performed before it counts itself in.
-__device__ __forceinline__ void consume_flush(ConsumeAcc acc, uint32_t seen, uint32_t arrivals, uint32_t arrivals_needed,
-                                              rdev_consume_result *out, uint32_t *s_max, uint64_t *s_sum) {
-    uint32_t m = acc.m;
-    uint64_t sum = acc.sum;
+// Workgroup part 1: fold the lanes' results; the workgroup's result is in thread 0 afterwards.  Call with all
+// kConsumeThreads lanes.
+__device__ __forceinline__ void consume_fold(const ConsumeAcc &acc, uint32_t *s_max, uint64_t *s_sum, uint32_t &m, uint64_t &sum) {
+    m = acc.m;
+    sum = acc.sum;
     for (int off = 32; off > 0; off >>= 1) {
         const uint32_t om = __shfl_down(m, off, 64);
         const uint64_t os = __shfl_down(sum, off, 64);
         m = om > m ? om : m;
         sum += os;
     }
-    __syncthreads();                                     // s_max / s_sum may still be read from an earlier flush
+    __syncthreads();                                     // s_max / s_sum may still be read from an earlier fold
     if ((threadIdx.x & 63) == 0) { s_max[threadIdx.x >> 6] = m; s_sum[threadIdx.x >> 6] = sum; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        for (uint32_t w = 1; w < kConsumeThreads / 64; ++w) { m = s_max[w] > m ? s_max[w] : m; sum += s_sum[w]; }
+    if (threadIdx.x < 64) {                              // the first wave folds the waves' results, one per lane
+        constexpr uint32_t kWaves = kConsumeThreads / 64;
+        m = threadIdx.x < kWaves ? s_max[threadIdx.x] : 0u;
+        sum = threadIdx.x < kWaves ? s_sum[threadIdx.x] : 0ull;
+        for (int off = kWaves / 2; off > 0; off >>= 1) {
+            const uint32_t om = __shfl_down(m, off, 64);
+            const uint64_t os = __shfl_down(sum, off, 64);
+            m = om > m ? om : m;
+            sum += os;
+        }
+    }
+}
+
+// Workgroup part 2: merge a workgroup's result for a tensor into *out and count `done` arrivals in; whoever brings the
+// count to `needed` publishes the result.  Called by all lanes of ONE wave; each lane with `active` set brings its own
+// tensor, so several tensors cost the wave the same two memory round trips as one.
+// Everything the workgroups exchange goes through agent-scope atomics, which are performed where all compute dies
+// meet; so no cache write-back or invalidation is needed around the arrival count, only that the lane's two
+// contributions have been performed before it counts itself in.
+__device__ __forceinline__ void consume_merge(bool active, rdev_consume_result *out, uint32_t m, uint64_t sum, uint32_t seen,
+                                              uint32_t done, uint32_t needed) {
+    if (active) {
         __hip_atomic_fetch_max((uint32_t *)&out->max, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_fetch_add((unsigned long long *)&out->word_sum, (unsigned long long)sum, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-        __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        wait_stores_acked();
-        __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (prev + arrivals == arrivals_needed) {        // last one: publish
+    }
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    wait_stores_acked();
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    if (active) {
+        const uint32_t prev = __hip_atomic_fetch_add(&out->_arrivals, done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + done == needed) {                     // last one: publish
             const uint32_t key = __hip_atomic_load((uint32_t *)&out->max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ((uint32_t *)&out->max)[0] = ord2f(key);
             out->seen_flag = seen;
@@ -602,22 +640,27 @@ __global__ __launch_bounds__(kConsumeThreads) void consume_reduce_max_kernel(con
         if (!seen) return;                              // status stays 1: every workgroup leaves
     }
     ConsumeAcc acc;
-    consume_accumulate(acc, payload, bytes, 0, bytes >> 4, (uint64_t)blockIdx.x * kConsumeThreads + threadIdx.x,
+    consume_accumulate(acc, payload, bytes, (uint64_t)blockIdx.x * kConsumeThreads, bytes >> 4,
                        (uint64_t)gridDim.x * kConsumeThreads, blockIdx.x == 0);
-    consume_flush(acc, seen, 1, gridDim.x, out, s_max, s_sum);
+    uint32_t m;
+    uint64_t sum;
+    consume_fold(acc, s_max, s_sum, m, sum);
+    if (threadIdx.x < 64) consume_merge(threadIdx.x == 0, out, m, sum, seen, 1, gridDim.x);
 }
 
 // The same for a list of tensors in one launch.  A tensor is cut into units of kConsumeUnitBytes; workgroup w takes
 // units w, w + grid, ... of the whole list in order, so tensors early in the list are reduced first.  A workgroup
-// keeps its lanes' results across the units of one tensor and merges them into the tensor's result once, when it
-// moves on to another tensor or runs out of units (merging per unit would queue thousands of atomics on the three
-// words of a large tensor's result).  With max_spins > 0 a workgroup first waits (bounded) for the in-arena flag of
-// each tensor it meets, which lets one launch follow a delivery that is still in flight: tensors whose flag is up are
-// reduced while later ones are still moving.  Units of a tensor whose wait ran out are skipped; its result keeps
-// status 1.  Every workgroup ends.
+// keeps its lanes' results across the units of one tensor; when it moves on to another tensor it folds them and puts
+// the tensor's result aside, and merges the results it has put aside - up to kConsumePending, one per lane - in one
+// go (merging per unit would queue thousands of atomics on the three words of a large tensor's result, merging per
+// tensor costs every workgroup two memory round trips for each tensor it touches).  With max_spins > 0 a workgroup
+// first waits (bounded) for the in-arena flag of each tensor it meets, which lets one launch follow a delivery that
+// is still in flight: tensors whose flag is up are reduced while later ones are still moving.  Units of a tensor whose
+// wait ran out are skipped; its result keeps status 1.  Every workgroup ends.
 constexpr uint32_t kConsumeBatchMax = 32;
-constexpr uint32_t kConsumeUnitBytes = 64 * 1024;
+constexpr uint32_t kConsumeUnitBytes = kConsumeThreads * kConsumeInFlight * 16;     // one round of loads
 constexpr uint32_t kConsumeTableMaxBlocks = 256;     // when the kernel may have to wait (waiting workgroups hold wave slots)
+constexpr uint32_t kConsumePending = 8;
 
 struct ConsumeEnt {
     const uint32_t *flag;
@@ -630,17 +673,45 @@ struct ConsumeBatch {
     ConsumeEnt e[kConsumeBatchMax];
     uint32_t n, n_units, max_spins, _pad;
 };
+struct ConsumePend {            // a workgroup's results of finished tensors that are still to be merged
+    rdev_consume_result *out[kConsumePending];
+    uint64_t sum[kConsumePending];
+    uint32_t m[kConsumePending], seen[kConsumePending], done[kConsumePending], needed[kConsumePending];
+};
 
 __global__ __launch_bounds__(kConsumeThreads) void consume_table_kernel(ConsumeBatch b, rdev_consume_result *out) {
     __shared__ uint32_t s_seen;
     __shared__ uint32_t s_max[kConsumeThreads / 64];
     __shared__ uint64_t s_sum[kConsumeThreads / 64];
-    uint32_t k = 0, cur = 0xFFFFFFFFu, seen = 0, done = 0;
+    __shared__ ConsumePend pend;
+    uint32_t k = 0, cur = 0xFFFFFFFFu, seen = 0, done = 0, n_pend = 0;
     ConsumeAcc acc;
+    auto merge_pending = [&]() {
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            const uint32_t j = threadIdx.x < n_pend ? threadIdx.x : 0;
+            consume_merge(threadIdx.x < n_pend, pend.out[j], pend.m[j], pend.sum[j], pend.seen[j], pend.done[j], pend.needed[j]);
+        }
+        n_pend = 0;
+    };
+    auto put_aside = [&]() {                                          // tensor `cur` is finished as far as this workgroup goes
+        uint32_t m;
+        uint64_t sum;
+        consume_fold(acc, s_max, s_sum, m, sum);
+        if (threadIdx.x == 0) {
+            pend.out[n_pend] = out + cur;
+            pend.m[n_pend] = m;
+            pend.sum[n_pend] = sum;
+            pend.seen[n_pend] = seen;
+            pend.done[n_pend] = done;
+            pend.needed[n_pend] = b.e[cur].n_units;
+        }
+        if (++n_pend == kConsumePending) merge_pending();
+    };
     for (uint32_t u = blockIdx.x; u < b.n_units; u += gridDim.x) {
         while (u >= b.e[k].first_unit + b.e[k].n_units) ++k;          // units ascend, so does the tensor
         if (k != cur) {                                               // on to another tensor
-            if (done) consume_flush(acc, seen, done, b.e[cur].n_units, out + cur, s_max, s_sum);
+            if (done) put_aside();
             acc = ConsumeAcc();
             done = 0;
             cur = k;
@@ -651,10 +722,11 @@ __global__ __launch_bounds__(kConsumeThreads) void consume_table_kernel(ConsumeB
         const uint32_t j = u - e.first_unit;
         const uint64_t nvec = e.bytes >> 4, per = kConsumeUnitBytes / 16;
         const uint64_t v0 = (uint64_t)j * per, v1 = v0 + per < nvec ? v0 + per : nvec;
-        consume_accumulate(acc, e.payload, e.bytes, v0, v1, threadIdx.x, kConsumeThreads, j + 1 == e.n_units);
+        consume_accumulate(acc, e.payload, e.bytes, v0, v1, kConsumeThreads, j + 1 == e.n_units);
         ++done;
     }
-    if (done) consume_flush(acc, seen, done, b.e[cur].n_units, out + cur, s_max, s_sum);
+    if (done) put_aside();
+    if (n_pend) merge_pending();
 }
 
 }  // namespace rdev

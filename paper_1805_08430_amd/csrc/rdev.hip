@@ -1535,7 +1535,7 @@ static rdev_status consume_checked(rdev_plan_t *plan, uint32_t idx, uint32_t max
     const rdev_placement &p = plan->pl[idx];
     hipLaunchKernelGGL(rdev::consume_init_kernel, dim3(1), dim3(64), 0, s, out, 1u);
     RDEV_TRY(launch_check("consume_init_kernel"));
-    const uint64_t per_block = (uint64_t)rdev::kConsumeThreads * 16 * 16;        // 64 KiB of payload per workgroup
+    const uint64_t per_block = rdev::kConsumeUnitBytes;                          // at least one full round of loads each
     const uint32_t cap = max_spins ? rdev::kConsumeMaxBlocks : rdev::kConsumeMaxBlocksNoWait;
     uint32_t grid = (uint32_t)std::min<uint64_t>(cap, (p.bytes + per_block - 1) / per_block);
     if (!grid) grid = 1;

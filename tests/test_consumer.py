@@ -176,7 +176,8 @@ def _check_results(got, o, ids, seen):
 def test_consume_batch_one_launch_for_a_list(name, groups):
     """rdev_consume_batch: (a) after the delivery, no waiting; (b) enqueued on a second stream right behind a
     delivery that is still in flight, every unit waiting for its tensor's in-arena flag; (c) nothing delivered:
-    every workgroup gives up after its spins and leaves, status 1.  Results equal the checker's exactly."""
+    every workgroup gives up after its spins and leaves, status 1; (d) on the delivery's own stream right behind it,
+    no wait and no host in between.  Results equal the checker's exactly."""
     import torch
     from gpu_harness import GpuRun
     wl = W.vgg16() if name == "vgg16" else W.small_mixed(63, n=40, max_bytes=2_000_000, n_recv=3, dtypes=("f32",), gran=4)
@@ -218,6 +219,20 @@ def test_consume_batch_one_launch_for_a_list(name, groups):
         cons.synchronize()
         _check_results(_results(res_v, n), o, ids, 10 + rnd)
         g.stream.synchronize()
+    # (d) on the delivery's own stream, right behind it: stream order stands in for the flags, nothing waits
+    for rnd in range(3):
+        assert R.rdev_poll(g.dev, g.plan, R.ALL_TENSORS, R.POLL_CONSUME, g.s)
+        for t in ids:
+            assert O.poll(o.dev, o.plan, t, consume=True)[0]
+        imgs = W.fill_sources(wl, variant=60 + rnd)
+        g.set_sources(imgs)
+        for sid, img in zip(o.send_ids, imgs):
+            o.image(sid)[:] = img
+        R.rdev_write_batch(g.dev, g.plan, None, R.ZEROCOPY, 20 + rnd, g.s)
+        R.rdev_consume_batch(g.dev, g.plan, ids, 0, base, g.s)
+        O.static_write(o.dev, o.plan, o.sources, 20 + rnd)
+        g.stream.synchronize()
+        _check_results(_results(res_v, n), o, ids, 0)
     for aid in o.recv_ids:
         assert np.array_equal(g.image(aid), o.image(aid))          # the consumer changes nothing in the arenas
     with pytest.raises(R.RdevError) as e:
