@@ -380,7 +380,7 @@ typedef struct {
 
 /* The light consumer of the paper's send/receive micro-benchmark (reduce_max,
  * section 5.1) for one static tensor whose size is a multiple of 4 bytes.
- * With max_spins > 0 a small grid (64 workgroups at most: waiting workgroups
+ * With max_spins > 0 a small grid (64 workgroups of 1024 lanes at most: waiting workgroups
  * occupy compute units, the cost section 3.5 warns of) first waits until the tensor's
  * in-arena flag is non-zero - at most max_spins polls per workgroup, a few
  * microseconds apart (about 14 us once it has been waiting for a while) - and
@@ -394,14 +394,17 @@ rdev_status rdev_consume_reduce_max(rdev_device_t *dev, rdev_plan_t *plan, uint3
                                     rdev_consume_result *out, void *stream);
 
 /* The same consumer for a list of static tensors in one launch per 32 tensors:
- * out[i] belongs to tensor_ids[i].  Tensors are cut into 64 KiB units that the
+ * out[i] belongs to tensor_ids[i].  Tensors are cut into 32 KiB units that the
  * workgroups take in list order, so tensors early in the list are reduced first.
+ * With max_spins == 0 nothing waits: enqueue it on the delivery's own stream right
+ * behind rdev_write_batch (stream order stands in for the flags; the cheapest way
+ * to consume a whole batch), or anywhere once the host has seen the flags.
  * With max_spins > 0 a workgroup first waits (at most max_spins polls, a few
  * microseconds apart) for the in-arena flag of each tensor it meets; enqueued on a second stream behind a delivery that
  * is still in flight, one launch then consumes each tensor as its flag comes up
  * (with flag_groups > 1 while later groups are still moving).  At most 256
- * workgroups wait at a time; they hold wave slots the copy could use (section
- * 3.5).  A tensor whose flag does not come up in time keeps status 1.  The flags
+ * workgroups of 1024 lanes wait at a time; they hold wave slots the copy could use
+ * (section 3.5: a copy beside them runs about a third slower).  A tensor whose flag does not come up in time keeps status 1.  The flags
  * are not cleared: consume them with rdev_poll afterwards.  For the waiting to
  * make progress the delivery must be on another stream, mapped to another
  * hardware queue, or already enqueued. */
