@@ -578,18 +578,12 @@ def main():
     for ts in sets:
         R.rdev_plan_profile(ts.plan, per_set, 1 << 30)      # create the events now; nothing is timed during warm-up
     run(a.warmup)
-    stream.synchronize()
-    stream2.synchronize()
-    stream_r.synchronize()
-    torch.cuda.synchronize()
+    torch.cuda.synchronize()                                # every stream of the device
     for ts in sets:
         R.rdev_plan_profile(ts.plan, per_set, time_every)   # re-arm only: the GPU does not sit idle before the timed region
     t0 = time.perf_counter()
     run(a.steps)
-    stream.synchronize()
-    stream2.synchronize()
-    stream_r.synchronize()
-    torch.cuda.synchronize()
+    torch.cuda.synchronize()                                # (a wait per stream first would add 10 us each to the timed region)
     t1 = time.perf_counter()
 
     kernel_ms = []
