@@ -472,10 +472,11 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const int64_t *__restr
 
 // ---- receiver-side consumer (sections 4, 5.1) ----
 
-// Launch shape: 1024-lane workgroups that stay and stride over the payload, four 16-byte loads in flight per lane,
-// two workgroups per compute unit at most.  Read-only 553 MB this way runs at 83 % of HBM peak; 256-lane workgroups
-// reach 78 % with 512 of them and 68 % with 2048, and a fresh workgroup per 64 KiB (whose two atomics per workgroup
-// then dominate) 32 %.  The arithmetic is free beside the loads (the same loop with one xor per word takes as long).
+// Launch shape: 1024-lane workgroups that stay and stride over the payload, two 16-byte loads in flight per lane,
+// two workgroups per compute unit at most.  Read-only 553 MB this way runs at 80 % of HBM peak (82 % with one or with
+// four loads in flight; two keep the kernel within 40 registers, see consume_accumulate); 256-lane workgroups reach
+// 78 % with 512 of them and 68 % with 2048, and a fresh workgroup per 64 KiB (whose two atomics per workgroup then
+// dominate) 32 %.  The arithmetic is free beside the loads (the same loop with one xor per word takes as long).
 constexpr uint32_t kConsumeThreads = 1024;
 constexpr uint32_t kConsumeInFlight = 2;
 constexpr uint32_t kConsumeMaxBlocks = 64;         // when the kernel waits for the flag on the device
