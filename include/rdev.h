@@ -303,10 +303,10 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
 
 /* The receiver's half of the dynamic protocol (section 3.3) without the host in
  * the loop: enqueued on `stream` behind the sender's metadata write (the same
- * stream, or one ordered after it), the kernels read each listed tensor's record
- * from its slot, clear the metadata flag, take round_up(bytes, align) from the
- * arena's dynamic heap in batch order, pull the payload from the sender's
- * address, record the offset in the slot and raise the payload-complete flag =
+ * stream, or one ordered after it), one kernel reads each listed tensor's record
+ * from its slot, clears the metadata flag, takes round_up(bytes, align) from the
+ * arena's dynamic heap in batch order, pulls the payload from the sender's
+ * address, records the offset in the slot and raises the payload-complete flag =
  * seq.  The arena ends up byte for byte as after rdev_poll(RDEV_POLL_META |
  * RDEV_POLL_CONSUME) + rdev_read_batch; no host poll of the metadata is needed,
  * and rdev_poll(tensor) later reports the payload as usual.
@@ -317,7 +317,9 @@ rdev_status rdev_read_batch(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xf
  * fails, nothing of the batch moves and no flag changes; rdev_recv_status tells.
  * The heap pointers then live on the device until the next rdev_dyn_reset:
  * rdev_read_batch of dynamic tensors and the RPC modes return RDEV_E_STATE in
- * between (allocations made through them earlier in the iteration are honoured). */
+ * between (allocations made through them earlier in the iteration are honoured).
+ * Calls on one plan must follow each other (one stream, or streams ordered by
+ * events): they share the plan's heap words and its count of finished workgroups. */
 rdev_status rdev_read_batch_device(rdev_device_t *dev, rdev_plan_t *plan, const rdev_xfer *x, uint32_t n,
                                    uint32_t seq, void *stream);
 /* How the device-side receives of this plan went.  *calls_made_out = calls of
